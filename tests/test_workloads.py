@@ -1,0 +1,58 @@
+"""Synthetic-input recipe: shapes, layer counts, FLOP totals, storage-grid snapping."""
+import numpy as np
+
+from oracle import oracle as orc
+from paper_2205_10357_amd import workloads as wl
+
+
+def test_resnet50_stack_has_53_convs_and_expected_flops():
+    ops = wl.resnet50_ops()
+    convs = [o for o in ops if o.op == "conv"]
+    assert len(convs) == 53 and sum(o.op == "maxpool" for o in ops) == 1
+    w = wl.Workload(4, "t", "bf16", 1, 224, 224, 3, ops, np.zeros((1, 3, 1, 1), np.float32), train=False)
+    shp = w.tensor_shapes()
+    assert shp[ops[-1].out] == (2048, 7, 7)
+    assert abs(w.flops_forward() / 1e9 - 8.17) < 0.01           # per image
+
+
+def test_bottleneck_and_stage2_flops():
+    w3 = wl.Workload(3, "t", "bf16", 64, 14, 14, 1024, wl.bottleneck14_ops(), np.zeros((1,), np.float32))
+    assert abs(w3.flops_step() / 1e9 - 83.85) < 0.01
+    w5 = wl.Workload(5, "t", "bf16", 128, 56, 56, 256, wl.stage2_ops(True), np.zeros((1,), np.float32))
+    assert len(w5.conv_blocks()) == 13 and abs(w5.flops_forward() / 1e9 - 263.07) < 0.01
+    w5u = wl.Workload(5, "t", "bf16", 128, 28, 28, 512, wl.stage2_ops(False), np.zeros((1,), np.float32))
+    assert len(w5u.conv_blocks()) == 12 and abs(w5u.flops_forward() / 1e9 - 223.61) < 0.01
+    w2 = wl.Workload(2, "t", "bf16", 32, 224, 224, 3, wl.resnet50_ops()[:1], np.zeros((1,), np.float32),
+                     need_input_grad=False)
+    assert abs(w2.flops_step() / 1e9 - 15.1) < 0.01
+
+
+def test_single_block_recipe():
+    w = wl.single_block_f32()
+    assert w.x.shape == (1, 16, 16, 16) and w.x.dtype == np.float32
+    assert w.x.min() >= 0 and w.x.max() < 1
+    p = w.params[0]
+    assert p["W"].shape == (16, 16, 3, 3)
+    assert np.array_equal(p["W"], wl.draw_weight(0, 16, 16, 3, 3))            # weight stream uses seed 0
+    assert abs(p["W"].std() - np.sqrt(2.0 / 144)) < 0.01
+    assert p["scale"].min() >= 0.5 and p["scale"].max() < 1.5
+    assert w.target.shape == (1, 16, 16, 16)
+    again = wl.single_block_f32()
+    assert np.array_equal(again.x, w.x) and np.array_equal(again.target, w.target)
+
+
+def test_streams_are_independent_per_tensor():
+    w = wl.bottleneck14_bf16(n=1, hw=4)
+    a, b = w.params[0]["W"], w.params[2]["W"]
+    assert a.shape == (256, 1024, 1, 1) and b.shape == (1024, 256, 1, 1)
+    assert not np.array_equal(a.ravel()[:64], b.ravel()[:64])
+
+
+def test_snap_to_bf16_agrees_with_checker_quantiser():
+    a = (np.random.default_rng(0).standard_normal(50000) * 3).astype(np.float32)
+    s = wl.snap_to_bf16(a)
+    assert np.array_equal(s.astype(np.float64), orc.quantize_bf16(a.astype(np.float64)))
+    assert np.array_equal(wl.snap_to_bf16(s), s)
+    bits = wl.bf16_bits(s)
+    assert bits.dtype == np.uint16
+    assert np.array_equal((bits.astype(np.uint32) << 16).view(np.float32), s)
