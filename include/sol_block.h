@@ -1,0 +1,131 @@
+/*
+ * sol_block.h -- C-ABI of the fused layer block
+ *
+ *      y = [ReLU]( scale[c] * conv(x, W)[.., c] + shift[c] [+ residual] )
+ *
+ * and of its backward pass, for one MI355X (gfx950).
+ *
+ * The paper (section "SOL principle") replaces step 1 of the training loop, the model
+ * forward pass, and step 3, the backward pass, by compiled code in which connected layers
+ * are merged (section "SOL architecture", the paragraph on grouping and layer merging);
+ * the framework keeps only memory allocation, the loss and the weight update.  For a
+ * ResNet-50-style network (the paper's benchmark model, section "SOL Benefits") the merged
+ * groups are exactly these blocks.  sol_block_fwd is step 1 for one block, sol_block_bwd is
+ * step 3 for one block.  The paper's three generated versions (inference, training forward,
+ * training backward) map to: fwd whose y is discarded later, fwd whose y is kept, bwd.
+ *
+ * Layout (all tensors dense, no strides):
+ *   activations  NHWC   x[N][H][W][C_in],  y / residual / dy / dres[N][Ho][Wo][C_out],
+ *                       dx / dx_addend[N][H][W][C_in]
+ *   weights      KRSC   W / dW[C_out][KH][KW][C_in]
+ *   Ho = (H + 2*pad - KH) / stride + 1, likewise Wo.   Cross-correlation, no bias,
+ *   dilation 1, groups 1, symmetric zero padding.
+ * Types:
+ *   SOL_BF16: x, W, residual, y, dy, dx, dres, dx_addend are bfloat16; scale, shift, dW,
+ *             dscale, dshift and every accumulator are float32.  One rounding (to nearest
+ *             even) at each bf16 store.
+ *   SOL_F32 : everything float32.
+ * Ownership: every pointer is a DEVICE pointer owned by the caller (16-byte aligned); the
+ *   library never allocates, frees or keeps device memory, never synchronises, and enqueues
+ *   only on the stream passed in (a hipStream_t, 0 = the null stream).  Inputs are read-only;
+ *   outputs are overwritten.  Outputs may not alias inputs (dx_addend == dx is allowed).
+ * Errors: every entry point returns 0 on success or a negative sol_status; nothing is
+ *   thrown, printed or aborted.  Argument checks are host-only and happen before any HIP
+ *   call, so a call that fails validation never touches the device.
+ * Thread safety: re-entrant; calls that share an output or workspace buffer race.
+ */
+#ifndef SOL_BLOCK_H
+#define SOL_BLOCK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SOL_API __attribute__((visibility("default")))
+
+typedef enum { SOL_F32 = 0, SOL_BF16 = 1 } sol_dtype;
+
+enum {
+    SOL_RELU = 1u << 0,          /* ReLU is the last operation of the block               */
+    SOL_DW_ACCUMULATE = 1u << 1  /* bwd adds into dW / dscale / dshift instead of storing */
+};
+
+typedef enum {
+    SOL_OK = 0,
+    SOL_ERR_NULL = -1,        /* a required pointer is NULL                                 */
+    SOL_ERR_SHAPE = -2,       /* non-positive size, stride < 1, pad < 0, empty output, ...  */
+    SOL_ERR_ALIGN = -3,       /* a pointer is not 16-byte aligned                           */
+    SOL_ERR_UNSUPPORTED = -4, /* unknown dtype / flag bits, tensor beyond 2^31-1 elements   */
+    SOL_ERR_WORKSPACE = -5,   /* workspace missing or smaller than sol_block_workspace_bytes */
+    SOL_ERR_LAUNCH = -6       /* the HIP runtime reported an error at launch                */
+} sol_status;
+
+typedef struct {
+    int32_t N, H, W, C_in;   /* x : [N][H][W][C_in]                 */
+    int32_t C_out, KH, KW;   /* W : [C_out][KH][KW][C_in]           */
+    int32_t stride, pad;     /* same in h and w                     */
+    int32_t dtype;           /* sol_dtype                           */
+    uint32_t flags;          /* SOL_RELU | SOL_DW_ACCUMULATE        */
+} sol_block_desc;
+
+enum { SOL_PASS_FWD = 0, SOL_PASS_BWD = 1 };
+
+/*
+ * Step 1 for one block (training-forward and inference versions are the same call):
+ *   z = conv(x, W);  v = scale[c]*z + shift[c] (+ residual);  y = ReLU ? max(v, 0) : v.
+ * residual may be NULL.  ws / ws_bytes: at least sol_block_workspace_bytes(desc, SOL_PASS_FWD)
+ * bytes (may be NULL when that is 0).
+ */
+SOL_API int sol_block_fwd(const sol_block_desc* desc, const void* x, const void* W, const float* scale,
+                  const float* shift, const void* residual, void* y, void* ws, size_t ws_bytes,
+                  void* hip_stream);
+
+/*
+ * Step 3 for one block.  With g = ReLU ? (y > 0 ? dy : 0) : dy  (the block's own stored
+ * output y decides the mask, which is why training must keep y between the passes -- the
+ * paper's remark on intermediate results in its section on memory consumption):
+ *   dx[n,hi,wi,ci]  = sum_{kh,kw,co} g[n,ho,wo,co] * scale[co] * W[co,kh,kw,ci]   (+ addend)
+ *   dW[co,kh,kw,ci] = scale[co] * sum_{n,ho,wo} g[n,ho,wo,co] * x[n,hi,wi,ci]
+ *   dshift[co]      = sum g[.,co]          dscale[co] = sum g[.,co] * conv(x,W)[.,co]
+ * Nullable: dx (skips the data gradient altogether), dres, dx_addend, dx_addend_mask.
+ *   dres            out, [N][Ho][Wo][C_out]: g itself (the gradient of the residual input).
+ *   dx_addend       in,  [N][H][W][C_in]: added to dx in the epilogue (shortcut gradients).
+ *   dx_addend_mask  in,  same shape as dx_addend: when given, only elements whose mask value
+ *                   is > 0 are added (lets a shortcut pass dy of the tail block together with
+ *                   that block's y instead of materialising its g).
+ * scale is required (dx and dW carry it); shift never enters a gradient.
+ * Results do not depend on run or launch order (no floating-point atomics).
+ */
+SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void* x, const void* W,
+                  const void* y, void* dx, float* dW, float* dscale, float* dshift,
+                  const float* scale, void* dres, const void* dx_addend,
+                  const void* dx_addend_mask, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Bytes of caller-provided scratch the given pass needs for this descriptor (0 if the
+ * descriptor is invalid: the pass itself then reports the error). */
+SOL_API size_t sol_block_workspace_bytes(const sol_block_desc* desc, int pass);
+
+/* Static, NUL-terminated description of a status code. */
+SOL_API const char* sol_status_string(int status);
+
+/*
+ * Glue that the paper leaves to the framework (loss, section "SOL principle") or that is not
+ * a convolution (the stem max-pool of the benchmark network); provided so that a whole
+ * training step can run without any framework kernel.  Same pointer / stream rules.
+ */
+
+/* dy = sign(y - t) / numel (sign(0) = 0): gradient of the mean absolute error. */
+SOL_API int sol_l1_loss_grad(int32_t dtype, const void* y, const void* t, void* dy, int64_t numel,
+                     void* hip_stream);
+
+/* Max-pool k x k / stride / pad over NHWC (padding never wins). */
+SOL_API int sol_maxpool_fwd(int32_t dtype, const void* x, void* y, int32_t N, int32_t H, int32_t W,
+                    int32_t C, int32_t k, int32_t stride, int32_t pad, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SOL_BLOCK_H */

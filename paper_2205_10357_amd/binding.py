@@ -1,0 +1,164 @@
+"""ctypes binding of libsol_block.so: the same entry points as include/sol_block.h.
+
+Argument marshalling only.  Every buffer argument may be a torch tensor (its
+``data_ptr()`` is used), any object with ``data_ptr()``, or an integer device address.
+There is no fallback: if the compiled library is missing, importing a symbol raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+SOL_F32, SOL_BF16 = 0, 1
+SOL_RELU, SOL_DW_ACCUMULATE = 1, 2
+SOL_PASS_FWD, SOL_PASS_BWD = 0, 1
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsol_block.so")
+EXPORTS = ("sol_block_fwd", "sol_block_bwd", "sol_block_workspace_bytes", "sol_status_string",
+           "sol_l1_loss_grad", "sol_maxpool_fwd")
+
+_lib = None
+
+
+class SolError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({sol_status_string(status)})")
+
+
+class _CDesc(C.Structure):
+    _fields_ = [("N", C.c_int32), ("H", C.c_int32), ("W", C.c_int32), ("C_in", C.c_int32),
+                ("C_out", C.c_int32), ("KH", C.c_int32), ("KW", C.c_int32),
+                ("stride", C.c_int32), ("pad", C.c_int32), ("dtype", C.c_int32), ("flags", C.c_uint32)]
+
+
+@dataclass(frozen=True)
+class BlockDesc:
+    N: int
+    H: int
+    W: int
+    C_in: int
+    C_out: int
+    KH: int
+    KW: int
+    stride: int
+    pad: int
+    dtype: int = SOL_BF16
+    flags: int = SOL_RELU
+
+    @property
+    def Ho(self) -> int:
+        return (self.H + 2 * self.pad - self.KH) // self.stride + 1
+
+    @property
+    def Wo(self) -> int:
+        return (self.W + 2 * self.pad - self.KW) // self.stride + 1
+
+    def c(self) -> _CDesc:
+        return _CDesc(self.N, self.H, self.W, self.C_in, self.C_out, self.KH, self.KW, self.stride,
+                      self.pad, self.dtype, self.flags)
+
+
+def lib():
+    """Load the compiled library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -m paper_2205_10357_amd.build` (there is no fallback path)")
+        l = C.CDLL(LIB_PATH)
+        vp, fp = C.c_void_p, C.c_void_p
+        l.sol_block_fwd.restype = C.c_int
+        l.sol_block_fwd.argtypes = [C.POINTER(_CDesc), vp, vp, fp, fp, vp, vp, vp, C.c_size_t, vp]
+        l.sol_block_bwd.restype = C.c_int
+        l.sol_block_bwd.argtypes = [C.POINTER(_CDesc), vp, vp, vp, vp, vp, fp, fp, fp, fp, vp, vp, vp, vp,
+                                    C.c_size_t, vp]
+        l.sol_block_workspace_bytes.restype = C.c_size_t
+        l.sol_block_workspace_bytes.argtypes = [C.POINTER(_CDesc), C.c_int]
+        l.sol_status_string.restype = C.c_char_p
+        l.sol_status_string.argtypes = [C.c_int]
+        l.sol_l1_loss_grad.restype = C.c_int
+        l.sol_l1_loss_grad.argtypes = [C.c_int32, vp, vp, vp, C.c_int64, vp]
+        l.sol_maxpool_fwd.restype = C.c_int
+        l.sol_maxpool_fwd.argtypes = [C.c_int32, vp, vp] + [C.c_int32] * 7 + [vp]
+        _lib = l
+    return _lib
+
+
+def _ptr(a) -> Optional[int]:
+    if a is None:
+        return None
+    if isinstance(a, int):
+        return a
+    if hasattr(a, "data_ptr"):
+        return int(a.data_ptr())
+    raise TypeError(f"cannot take a device address from {type(a)!r}")
+
+
+def _nbytes(a) -> int:
+    if a is None:
+        return 0
+    return int(a.numel() * a.element_size())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream) or None
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None
+
+
+def _cdesc(desc) -> _CDesc:
+    return desc.c() if isinstance(desc, BlockDesc) else desc
+
+
+def sol_status_string(status: int) -> str:
+    return lib().sol_status_string(int(status)).decode()
+
+
+def sol_block_workspace_bytes(desc, pass_: int) -> int:
+    d = _cdesc(desc)
+    return int(lib().sol_block_workspace_bytes(C.byref(d), int(pass_)))
+
+
+def sol_block_fwd(desc, x, W, scale, shift, residual, y, ws=None, ws_bytes: Optional[int] = None, stream=None,
+                  check: bool = True) -> int:
+    d = _cdesc(desc)
+    nb = _nbytes(ws) if ws_bytes is None else ws_bytes
+    st = lib().sol_block_fwd(C.byref(d), _ptr(x), _ptr(W), _ptr(scale), _ptr(shift), _ptr(residual), _ptr(y),
+                             _ptr(ws), nb, _stream(stream))
+    if check and st != 0:
+        raise SolError(st, "sol_block_fwd")
+    return st
+
+
+def sol_block_bwd(desc, dy, x, W, y, dx, dW, dscale, dshift, scale, dres=None, dx_addend=None,
+                  dx_addend_mask=None, ws=None, ws_bytes: Optional[int] = None, stream=None,
+                  check: bool = True) -> int:
+    d = _cdesc(desc)
+    nb = _nbytes(ws) if ws_bytes is None else ws_bytes
+    st = lib().sol_block_bwd(C.byref(d), _ptr(dy), _ptr(x), _ptr(W), _ptr(y), _ptr(dx), _ptr(dW), _ptr(dscale),
+                             _ptr(dshift), _ptr(scale), _ptr(dres), _ptr(dx_addend), _ptr(dx_addend_mask),
+                             _ptr(ws), nb, _stream(stream))
+    if check and st != 0:
+        raise SolError(st, "sol_block_bwd")
+    return st
+
+
+def sol_l1_loss_grad(dtype: int, y, t, dy, numel: int, stream=None, check: bool = True) -> int:
+    st = lib().sol_l1_loss_grad(int(dtype), _ptr(y), _ptr(t), _ptr(dy), int(numel), _stream(stream))
+    if check and st != 0:
+        raise SolError(st, "sol_l1_loss_grad")
+    return st
+
+
+def sol_maxpool_fwd(dtype: int, x, y, N: int, H: int, W: int, Cc: int, k: int, stride: int, pad: int, stream=None,
+                    check: bool = True) -> int:
+    st = lib().sol_maxpool_fwd(int(dtype), _ptr(x), _ptr(y), N, H, W, Cc, k, stride, pad, _stream(stream))
+    if check and st != 0:
+        raise SolError(st, "sol_maxpool_fwd")
+    return st

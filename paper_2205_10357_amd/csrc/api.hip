@@ -1,0 +1,375 @@
+// C-ABI of the fused block: argument validation (host only, before any HIP call), launch
+// planning (tile shape, split count, workspace layout) and the calls into the kernels.
+#include <stdlib.h>
+#include <string.h>
+
+#include "../../include/sol_block.h"
+#include "classes.h"
+#include "launch.h"
+
+namespace sol {
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+struct Geometry {
+    int Ho, Wo;
+    long long M, K;
+    long long x_elems, y_elems, w_elems;
+};
+
+int check_desc(const sol_block_desc* d, Geometry* g) {
+    if (!d) return SOL_ERR_NULL;
+    if (d->dtype != SOL_F32 && d->dtype != SOL_BF16) return SOL_ERR_UNSUPPORTED;
+    if (d->flags & ~(uint32_t)(SOL_RELU | SOL_DW_ACCUMULATE)) return SOL_ERR_UNSUPPORTED;
+    if (d->N < 1 || d->H < 1 || d->W < 1 || d->C_in < 1 || d->C_out < 1 || d->KH < 1 || d->KW < 1 ||
+        d->stride < 1 || d->pad < 0)
+        return SOL_ERR_SHAPE;
+    if (d->H + 2 * (long long)d->pad < d->KH || d->W + 2 * (long long)d->pad < d->KW) return SOL_ERR_SHAPE;
+    g->Ho = (d->H + 2 * d->pad - d->KH) / d->stride + 1;
+    g->Wo = (d->W + 2 * d->pad - d->KW) / d->stride + 1;
+    g->M = (long long)d->N * g->Ho * g->Wo;
+    g->K = (long long)d->KH * d->KW * d->C_in;
+    g->x_elems = (long long)d->N * d->H * d->W * d->C_in;
+    g->y_elems = g->M * d->C_out;
+    g->w_elems = g->K * d->C_out;
+    const long long lim = 0x7fffffffLL;
+    if (g->x_elems > lim || g->y_elems > lim || g->w_elems > lim) return SOL_ERR_UNSUPPORTED;
+    return SOL_OK;
+}
+
+int env_int(const char* name, int fallback) {
+    const char* v = getenv(name);
+    if (!v || !*v) return fallback;
+    return atoi(v);
+}
+
+// Largest tile that still yields about one workgroup per compute unit; small problems fall
+// back to the smallest tile.  SOL_IGEMM_TILE overrides (tuning experiments).
+int pick_igemm_tile(const long long* class_rows, int ncls, int Nc) {
+    const int forced = env_int("SOL_IGEMM_TILE", -1);
+    if (forced >= 0 && forced <= 3) return forced;
+    const int order_wide[4] = {1, 0, 2, 3};
+    const int order_narrow[2] = {2, 3};
+    const int* order = Nc > 64 ? order_wide : order_narrow;
+    const int n = Nc > 64 ? 4 : 2;
+    for (int i = 0; i < n; ++i) {
+        int bp, bc;
+        igemm_tile_shape(order[i], &bp, &bc);
+        long long tiles = 0;
+        for (int c = 0; c < ncls; ++c) tiles += (class_rows[c] + bp - 1) / bp;
+        tiles *= (Nc + bc - 1) / bc;
+        if (tiles >= 192) return order[i];
+    }
+    return order[n - 1];
+}
+
+struct BwdPlan {
+    int splits, m_per_split, tiles_k, tiles_c;
+    size_t wpack_off, part_off, dshift_off, total;
+};
+
+BwdPlan plan_bwd(const sol_block_desc* d, const Geometry& g) {
+    BwdPlan b{};
+    if (d->dtype == SOL_F32) {
+        b.splits = 1;
+        b.m_per_split = (int)g.M;
+        b.wpack_off = 0;
+        b.part_off = 0;
+    } else {
+        b.tiles_k = (int)((g.K + 127) / 128);
+        b.tiles_c = (d->C_out + 127) / 128;
+        const long long tiles = (long long)b.tiles_k * b.tiles_c;
+        const long long max_splits = (g.M + 127) / 128;
+        long long want = env_int("SOL_WGRAD_SPLITS", 0);
+        if (want <= 0) {
+            want = (512 + tiles - 1) / tiles;
+            // keep the fp32 partials below ~64 MiB
+            const long long cap = (64LL << 20) / (g.w_elems * 4 > 0 ? g.w_elems * 4 : 1);
+            if (want > cap) want = cap;
+        }
+        if (want < 1) want = 1;
+        if (want > max_splits) want = max_splits;
+        long long mps = (g.M + want - 1) / want;
+        mps = (mps + 127) / 128 * 128;
+        b.m_per_split = (int)mps;
+        b.splits = (int)((g.M + mps - 1) / mps);
+        b.wpack_off = 0;
+        b.part_off = align_up((size_t)g.w_elems * 2);
+    }
+    b.dshift_off = b.part_off + align_up((size_t)b.splits * g.w_elems * 4);
+    b.total = b.dshift_off + align_up((size_t)b.splits * d->C_out * 4);
+    return b;
+}
+
+int fwd_bf16(const sol_block_desc* d, const Geometry& g, const void* x, const void* W, const float* scale,
+             const float* shift, const void* residual, void* y, hipStream_t stream) {
+    IgemmParams p{};
+    p.src = (const bf16_t*)x;
+    p.src_mask = nullptr;
+    p.wmat = (const bf16_t*)W;
+    p.out = (bf16_t*)y;
+    p.scale = scale;
+    p.shift = shift;
+    p.addend = (const bf16_t*)residual;
+    p.addend_mask = nullptr;
+    p.Hs = d->H;
+    p.Ws = d->W;
+    p.Cs = d->C_in;
+    p.Nc = d->C_out;
+    p.Hout = g.Ho;
+    p.Wout = g.Wo;
+    p.relu = (d->flags & SOL_RELU) ? 1 : 0;
+    p.ncls = 1;
+    RowClass& c = p.cls[0];
+    c.rows = (int)g.M;
+    c.Rh = g.Ho;
+    c.Rw = g.Wo;
+    c.h_mul = d->stride;
+    c.h_off = -d->pad;
+    c.w_mul = d->stride;
+    c.w_off = -d->pad;
+    c.Th = d->KH;
+    c.Tw = d->KW;
+    c.tap_step = 1;
+    c.oh_mul = 1;
+    c.oh_off = 0;
+    c.ow_mul = 1;
+    c.ow_off = 0;
+    c.tile_begin = 0;
+    c.b_off = 0;
+    const long long rows[1] = {g.M};
+    const int tile = pick_igemm_tile(rows, 1, d->C_out);
+    int bp, bc;
+    igemm_tile_shape(tile, &bp, &bc);
+    p.tiles_c = (d->C_out + bc - 1) / bc;
+    p.total_tiles = (int)((g.M + bp - 1) / bp) * p.tiles_c;
+    const bool vec = (d->C_in % 8) == 0;
+    return launch_igemm(p, tile, vec, false, stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
+}
+
+int dgrad_bf16(const sol_block_desc* d, const Geometry& g, const void* dy, const void* y, const bf16_t* wpack,
+               void* dx, const void* addend, const void* addend_mask, hipStream_t stream) {
+    const int s = d->stride;
+    IgemmParams p{};
+    const bool relu = (d->flags & SOL_RELU) != 0;
+    p.src = (const bf16_t*)dy;
+    p.src_mask = relu ? (const bf16_t*)y : nullptr;
+    p.wmat = wpack;
+    p.out = (bf16_t*)dx;
+    p.scale = nullptr;
+    p.shift = nullptr;
+    p.addend = (const bf16_t*)addend;
+    p.addend_mask = (const bf16_t*)addend_mask;
+    p.Hs = g.Ho;
+    p.Ws = g.Wo;
+    p.Cs = d->C_out;
+    p.Nc = d->C_in;
+    p.Hout = d->H;
+    p.Wout = d->W;
+    p.relu = 0;
+    long long rows[kMaxClasses];
+    int nc = 0;
+    for (int ph = 0; ph < s; ++ph)
+        for (int pw = 0; pw < s; ++pw) {
+            const int Rh = d->H > ph ? (d->H - ph + s - 1) / s : 0;
+            const int Rw = d->W > pw ? (d->W - pw + s - 1) / s : 0;
+            if (Rh == 0 || Rw == 0) continue;
+            int fh, fw;
+            RowClass& c = p.cls[nc];
+            c.Th = class_taps(d->KH, s, d->pad, ph, &fh);
+            c.Tw = class_taps(d->KW, s, d->pad, pw, &fw);
+            if (c.Th == 0 || c.Tw == 0) {   // no tap reaches these pixels: K = 0, output = addend
+                c.Th = 0;
+                c.Tw = 1;
+            }
+            c.rows = d->N * Rh * Rw;
+            c.Rh = Rh;
+            c.Rw = Rw;
+            c.h_mul = 1;
+            c.h_off = (ph + d->pad - fh) / s;
+            c.w_mul = 1;
+            c.w_off = (pw + d->pad - fw) / s;
+            c.tap_step = -1;
+            c.oh_mul = s;
+            c.oh_off = ph;
+            c.ow_mul = s;
+            c.ow_off = pw;
+            c.b_off = class_weight_offset(d->C_in, d->C_out, d->KH, d->KW, s, d->pad, ph, pw);
+            rows[nc] = c.rows;
+            ++nc;
+        }
+    p.ncls = nc;
+    const int tile = pick_igemm_tile(rows, nc, d->C_in);
+    int bp, bc;
+    igemm_tile_shape(tile, &bp, &bc);
+    p.tiles_c = (d->C_in + bc - 1) / bc;
+    int tiles_p = 0;
+    for (int c = 0; c < nc; ++c) {
+        p.cls[c].tile_begin = tiles_p;
+        tiles_p += (int)((rows[c] + bp - 1) / bp);
+    }
+    p.total_tiles = tiles_p * p.tiles_c;
+    const bool vec = (d->C_out % 8) == 0;
+    return launch_igemm(p, tile, vec, relu, stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
+}
+
+}  // namespace
+}  // namespace sol
+
+using namespace sol;
+
+extern "C" {
+
+SOL_API const char* sol_status_string(int status) {
+    switch (status) {
+        case SOL_OK: return "ok";
+        case SOL_ERR_NULL: return "a required pointer is NULL";
+        case SOL_ERR_SHAPE: return "invalid shape, stride or padding";
+        case SOL_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case SOL_ERR_UNSUPPORTED: return "unsupported dtype, flag or size";
+        case SOL_ERR_WORKSPACE: return "workspace missing or too small";
+        case SOL_ERR_LAUNCH: return "HIP launch error";
+        default: return "unknown status";
+    }
+}
+
+SOL_API size_t sol_block_workspace_bytes(const sol_block_desc* desc, int pass) {
+    Geometry g;
+    if (check_desc(desc, &g) != SOL_OK) return 0;
+    if (pass == SOL_PASS_FWD) return 0;
+    if (pass != SOL_PASS_BWD) return 0;
+    return plan_bwd(desc, g).total;
+}
+
+SOL_API int sol_block_fwd(const sol_block_desc* desc, const void* x, const void* W, const float* scale, const float* shift,
+                  const void* residual, void* y, void* ws, size_t ws_bytes, void* hip_stream) {
+    (void)ws;
+    (void)ws_bytes;
+    Geometry g;
+    if (int e = check_desc(desc, &g); e != SOL_OK) return e;
+    if (!x || !W || !scale || !shift || !y) return SOL_ERR_NULL;
+    if (misaligned(x) || misaligned(W) || misaligned(scale) || misaligned(shift) || misaligned(y) ||
+        misaligned(residual))
+        return SOL_ERR_ALIGN;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (desc->dtype == SOL_BF16) return fwd_bf16(desc, g, x, W, scale, shift, residual, y, stream);
+    DirectParams p{};
+    p.x = (const float*)x;
+    p.W = (const float*)W;
+    p.scale = scale;
+    p.shift = shift;
+    p.res = (const float*)residual;
+    p.y = (float*)y;
+    p.N = desc->N; p.H = desc->H; p.W_ = desc->W; p.C_in = desc->C_in; p.C_out = desc->C_out;
+    p.KH = desc->KH; p.KW = desc->KW; p.stride = desc->stride; p.pad = desc->pad;
+    p.Ho = g.Ho; p.Wo = g.Wo; p.relu = (desc->flags & SOL_RELU) ? 1 : 0;
+    return launch_direct_fwd_f32(p, stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
+}
+
+SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void* x, const void* W, const void* y, void* dx,
+                  float* dW, float* dscale, float* dshift, const float* scale, void* dres, const void* dx_addend,
+                  const void* dx_addend_mask, void* ws, size_t ws_bytes, void* hip_stream) {
+    Geometry g;
+    if (int e = check_desc(desc, &g); e != SOL_OK) return e;
+    const bool relu = (desc->flags & SOL_RELU) != 0;
+    if (!dy || !x || !W || !dW || !dscale || !dshift || !scale) return SOL_ERR_NULL;
+    if (relu && !y) return SOL_ERR_NULL;
+    if (dx_addend_mask && !dx_addend) return SOL_ERR_NULL;
+    if (misaligned(dy) || misaligned(x) || misaligned(W) || misaligned(y) || misaligned(dx) || misaligned(dW) ||
+        misaligned(dscale) || misaligned(dshift) || misaligned(scale) || misaligned(dres) ||
+        misaligned(dx_addend) || misaligned(dx_addend_mask) || misaligned(ws))
+        return SOL_ERR_ALIGN;
+    if (desc->dtype == SOL_BF16 && dx && desc->stride * desc->stride > kMaxClasses) return SOL_ERR_UNSUPPORTED;
+    const BwdPlan plan = plan_bwd(desc, g);
+    if (!ws || ws_bytes < plan.total) return SOL_ERR_WORKSPACE;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    unsigned char* wsb = (unsigned char*)ws;
+    float* partial = (float*)(wsb + plan.part_off);
+    float* dshift_partial = (float*)(wsb + plan.dshift_off);
+    const void* ymask = relu ? y : nullptr;
+
+    if (dres) {
+        if (launch_masked_copy(desc->dtype, dy, ymask, dres, g.y_elems, stream) != hipSuccess) return SOL_ERR_LAUNCH;
+    }
+
+    if (desc->dtype == SOL_BF16) {
+        if (dx) {
+            bf16_t* wpack = (bf16_t*)(wsb + plan.wpack_off);
+            PackParams pk{(const bf16_t*)W, scale, wpack, desc->C_in, desc->C_out, desc->KH, desc->KW,
+                          desc->stride, desc->pad};
+            if (launch_pack_dgrad_weights(pk, stream) != hipSuccess) return SOL_ERR_LAUNCH;
+            if (int e = dgrad_bf16(desc, g, dy, y, wpack, dx, dx_addend, dx_addend_mask, stream); e != SOL_OK)
+                return e;
+        }
+        WgradParams wp{};
+        wp.dy = (const bf16_t*)dy;
+        wp.y = (const bf16_t*)ymask;
+        wp.x = (const bf16_t*)x;
+        wp.partial = partial;
+        wp.dshift_partial = dshift_partial;
+        wp.N = desc->N; wp.H = desc->H; wp.W = desc->W; wp.C_in = desc->C_in; wp.C_out = desc->C_out;
+        wp.KH = desc->KH; wp.KW = desc->KW; wp.stride = desc->stride; wp.pad = desc->pad;
+        wp.Ho = g.Ho; wp.Wo = g.Wo; wp.M = (int)g.M; wp.K = (int)g.K;
+        wp.splits = plan.splits; wp.m_per_split = plan.m_per_split;
+        wp.tiles_k = plan.tiles_k; wp.tiles_c = plan.tiles_c;
+        const bool vec = (desc->C_in % 8) == 0 && (desc->C_out % 8) == 0;
+        if (launch_wgrad(wp, vec, relu, stream) != hipSuccess) return SOL_ERR_LAUNCH;
+    } else {
+        DirectParams p{};
+        p.x = (const float*)x;
+        p.W = (const float*)W;
+        p.scale = scale;
+        p.dy = (const float*)dy;
+        p.ymask = (const float*)ymask;
+        p.dx = (float*)dx;
+        p.addend = (const float*)dx_addend;
+        p.addend_mask = (const float*)dx_addend_mask;
+        p.G = partial;
+        p.dshift_partial = dshift_partial;
+        p.N = desc->N; p.H = desc->H; p.W_ = desc->W; p.C_in = desc->C_in; p.C_out = desc->C_out;
+        p.KH = desc->KH; p.KW = desc->KW; p.stride = desc->stride; p.pad = desc->pad;
+        p.Ho = g.Ho; p.Wo = g.Wo; p.relu = relu ? 1 : 0;
+        if (dx && launch_direct_dgrad_f32(p, stream) != hipSuccess) return SOL_ERR_LAUNCH;
+        if (launch_direct_wgrad_f32(p, stream) != hipSuccess) return SOL_ERR_LAUNCH;
+    }
+
+    ReduceParams rp{};
+    rp.partial = partial;
+    rp.dshift_partial = dshift_partial;
+    rp.W = W;
+    rp.scale = scale;
+    rp.dW = dW;
+    rp.dscale = dscale;
+    rp.dshift = dshift;
+    rp.C_out = desc->C_out;
+    rp.K = (int)g.K;
+    rp.splits = plan.splits;
+    rp.accumulate = (desc->flags & SOL_DW_ACCUMULATE) ? 1 : 0;
+    rp.w_is_bf16 = desc->dtype == SOL_BF16 ? 1 : 0;
+    return launch_wgrad_reduce(rp, stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
+}
+
+SOL_API int sol_l1_loss_grad(int32_t dtype, const void* y, const void* t, void* dy, int64_t numel, void* hip_stream) {
+    if (dtype != SOL_F32 && dtype != SOL_BF16) return SOL_ERR_UNSUPPORTED;
+    if (numel < 1) return SOL_ERR_SHAPE;
+    if (!y || !t || !dy) return SOL_ERR_NULL;
+    if (misaligned(y) || misaligned(t) || misaligned(dy)) return SOL_ERR_ALIGN;
+    return launch_l1_grad(dtype, y, t, dy, numel, (hipStream_t)hip_stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
+}
+
+SOL_API int sol_maxpool_fwd(int32_t dtype, const void* x, void* y, int32_t N, int32_t H, int32_t W, int32_t C, int32_t k,
+                    int32_t stride, int32_t pad, void* hip_stream) {
+    if (dtype != SOL_F32 && dtype != SOL_BF16) return SOL_ERR_UNSUPPORTED;
+    if (N < 1 || H < 1 || W < 1 || C < 1 || k < 1 || stride < 1 || pad < 0 || pad >= k || H + 2 * pad < k ||
+        W + 2 * pad < k)
+        return SOL_ERR_SHAPE;
+    if (!x || !y) return SOL_ERR_NULL;
+    if (misaligned(x) || misaligned(y)) return SOL_ERR_ALIGN;
+    return launch_maxpool(dtype, x, y, N, H, W, C, k, stride, pad, (hipStream_t)hip_stream) == hipSuccess
+               ? SOL_OK : SOL_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,118 @@
+// Shared declarations of the gfx950 kernels: vector types, bf16 helpers, launch parameter
+// blocks.  Device code only sees plain structs passed by value; the host planner fills them.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sol {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef short shortx8 __attribute__((ext_vector_type(8)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+
+typedef uint16_t bf16_t;   // storage type of one bfloat16 element
+
+constexpr int kWave = 64;
+
+// ---- bf16 <-> f32 (round to nearest even on the way down) -------------------------------
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);   // quiet NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// Per 16-bit lane: keep v where the bf16 value m is > 0, else +0.   (bf16 > 0  <=>  the
+// pattern read as a signed 16-bit integer is > 0; NaNs do not occur in stored activations.)
+__device__ __forceinline__ uintx4 mask_where_positive(uintx4 v, uintx4 m) {
+    shortx8 ms = __builtin_bit_cast(shortx8, m);
+    shortx8 keep = ms > (short)0;            // all-ones / zero per lane
+    shortx8 vs = __builtin_bit_cast(shortx8, v);
+    return __builtin_bit_cast(uintx4, (shortx8)(vs & keep));
+}
+__device__ __forceinline__ uintx2 mask_where_positive(uintx2 v, uintx2 m) {
+    shortx4 ms = __builtin_bit_cast(shortx4, m);
+    shortx4 keep = ms > (short)0;
+    shortx4 vs = __builtin_bit_cast(shortx4, v);
+    return __builtin_bit_cast(uintx2, (shortx4)(vs & keep));
+}
+
+// ---- implicit-GEMM launch parameters -----------------------------------------------------
+// One "row class" describes which GEMM rows (pixels) a group of workgroups produces and how a
+// row and a filter tap map to a source pixel.  The forward pass has one class; the data
+// gradient of a stride-s block has s*s classes (input pixels grouped by their residue mod s,
+// each with only the taps that can reach it).
+struct RowClass {
+    int rows;               // GEMM rows of this class = N * Rh * Rw
+    int Rh, Rw;             // rows per image
+    int h_mul, h_off;       // source row   = rh * h_mul + h_off + th * tap_step
+    int w_mul, w_off;       // source col   = rw * w_mul + w_off + tw * tap_step
+    int Th, Tw;             // taps of this class
+    int tap_step;           // +1 (forward) or -1 (data gradient)
+    int oh_mul, oh_off;     // output row   = rh * oh_mul + oh_off
+    int ow_mul, ow_off;     // output col   = rw * ow_mul + ow_off
+    int tile_begin;         // index of this class' first pixel tile in the launch
+    long long b_off;        // element offset of this class' weight matrix [Nc][Th*Tw*Cs]
+};
+
+constexpr int kMaxClasses = 4;
+
+struct IgemmParams {
+    const bf16_t* src;          // gathered activation: x (forward) or dy (data gradient)
+    const bf16_t* src_mask;     // data gradient with ReLU: the block's y (mask y > 0); else null
+    const bf16_t* wmat;         // weight matrices, K-contiguous rows
+    bf16_t* out;                // y or dx, [N][Hout][Wout][Nc]
+    const float* scale;         // forward epilogue (null in the data gradient)
+    const float* shift;
+    const bf16_t* addend;       // residual (forward) / dx_addend (data gradient); may be null
+    const bf16_t* addend_mask;  // optional gate of the addend (mask value > 0)
+    int Hs, Ws, Cs;             // source image height, width, channels
+    int Nc;                     // GEMM columns = output channels of this GEMM
+    int Hout, Wout;             // output image
+    int relu;                   // forward: clamp at 0
+    int ncls;
+    int tiles_c;                // channel tiles per pixel tile
+    int total_tiles;
+    RowClass cls[kMaxClasses];
+};
+
+// ---- weight-gradient launch parameters ---------------------------------------------------
+struct WgradParams {
+    const bf16_t* dy;           // [M][C_out]
+    const bf16_t* y;            // mask source (null when the block has no ReLU)
+    const bf16_t* x;            // [N][H][W][C_in]
+    float* partial;             // [splits][C_out][K] fp32
+    float* dshift_partial;      // [splits][C_out] fp32
+    int N, H, W, C_in, C_out, KH, KW, stride, pad, Ho, Wo;
+    int M;                      // N*Ho*Wo
+    int K;                      // KH*KW*C_in
+    int splits;
+    int m_per_split;            // multiple of the reduction tile
+    int tiles_k, tiles_c;
+};
+
+struct ReduceParams {
+    const float* partial;       // [splits][C_out][K]
+    const float* dshift_partial;// [splits][C_out]
+    const void* W;              // [C_out][K] (bf16 or f32)
+    const float* scale;
+    float* dW;
+    float* dscale;
+    float* dshift;
+    int C_out, K, splits, accumulate, w_is_bf16;
+};
+
+}  // namespace sol

@@ -1,0 +1,131 @@
+// Small memory-bound helpers around the two GEMM kernels: weight re-packing for the data
+// gradient, the masked gradient copy (dres), the L1-loss gradient and the stem max-pool.
+#include "launch.h"
+#include "classes.h"
+
+namespace sol {
+
+// out[class][ci][(jh*Tw + jw)*C_out + co] = bf16(scale[co] * W[co][kh][kw][ci]); one thread per
+// weight element, indexed so that writes are contiguous in co.
+__global__ __launch_bounds__(256) void pack_dgrad_weights_kernel(const PackParams p) {
+    const long long total = (long long)p.C_out * p.KH * p.KW * p.C_in;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int co = (int)(idx % p.C_out);
+    long long r = idx / p.C_out;
+    const int ci = (int)(r % p.C_in);
+    r /= p.C_in;
+    const int kw = (int)(r % p.KW);
+    const int kh = (int)(r / p.KW);
+    const int s = p.stride;
+    const int ph = ((kh - p.pad) % s + s) % s, pw = ((kw - p.pad) % s + s) % s;
+    int fh, fw;
+    const int Th = class_taps(p.KH, s, p.pad, ph, &fh), Tw = class_taps(p.KW, s, p.pad, pw, &fw);
+    const long long off = class_weight_offset(p.C_in, p.C_out, p.KH, p.KW, s, p.pad, ph, pw);
+    const int jh = (kh - fh) / s, jw = (kw - fw) / s;
+    const float w = bf16_to_f32(p.W[(((long long)co * p.KH + kh) * p.KW + kw) * p.C_in + ci]);
+    p.out[off + ((long long)ci * Th * Tw + (jh * Tw + jw)) * p.C_out + co] = f32_to_bf16(p.scale[co] * w);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void masked_copy_kernel(const T* dy, const T* y, T* dres, long long numel) {
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= numel) return;
+    if constexpr (sizeof(T) == 2) {
+        dres[i] = (!y || (short)y[i] > 0) ? dy[i] : (T)0;
+    } else {
+        dres[i] = (!y || y[i] > 0.f) ? dy[i] : (T)0;
+    }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void l1_grad_kernel(const void* yv, const void* tv, void* dyv, long long numel,
+                                                      float inv) {
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= numel) return;
+    float y, t;
+    if constexpr (BF16) {
+        y = bf16_to_f32(reinterpret_cast<const bf16_t*>(yv)[i]);
+        t = bf16_to_f32(reinterpret_cast<const bf16_t*>(tv)[i]);
+    } else {
+        y = reinterpret_cast<const float*>(yv)[i];
+        t = reinterpret_cast<const float*>(tv)[i];
+    }
+    const float d = y > t ? inv : (y < t ? -inv : 0.f);
+    if constexpr (BF16) reinterpret_cast<bf16_t*>(dyv)[i] = f32_to_bf16(d);
+    else reinterpret_cast<float*>(dyv)[i] = d;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void maxpool_kernel(const void* xv, void* yv, int N, int H, int W, int C, int k,
+                                                      int stride, int pad, int Ho, int Wo) {
+    const long long total = (long long)N * Ho * Wo * C;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int c = (int)(idx % C);
+    long long pix = idx / C;
+    const int wo = (int)(pix % Wo);
+    pix /= Wo;
+    const int ho = (int)(pix % Ho);
+    const int n = (int)(pix / Ho);
+    float m = -INFINITY;
+    for (int kh = 0; kh < k; ++kh) {
+        const int hi = ho * stride - pad + kh;
+        if ((unsigned)hi >= (unsigned)H) continue;
+        for (int kw = 0; kw < k; ++kw) {
+            const int wi = wo * stride - pad + kw;
+            if ((unsigned)wi >= (unsigned)W) continue;
+            const long long o = (((long long)n * H + hi) * W + wi) * C + c;
+            const float v = BF16 ? bf16_to_f32(reinterpret_cast<const bf16_t*>(xv)[o])
+                                 : reinterpret_cast<const float*>(xv)[o];
+            m = v > m ? v : m;
+        }
+    }
+    if constexpr (BF16) reinterpret_cast<bf16_t*>(yv)[idx] = f32_to_bf16(m);
+    else reinterpret_cast<float*>(yv)[idx] = m;
+}
+
+static inline unsigned blocks_for(long long total) { return (unsigned)((total + 255) / 256); }
+
+hipError_t launch_pack_dgrad_weights(const PackParams& p, hipStream_t s) {
+    const long long total = (long long)p.C_out * p.KH * p.KW * p.C_in;
+    hipLaunchKernelGGL(pack_dgrad_weights_kernel, dim3(blocks_for(total)), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_masked_copy(int dtype, const void* dy, const void* y, void* dres, long long numel, hipStream_t s) {
+    if (numel <= 0) return hipSuccess;
+    if (dtype == 1)
+        hipLaunchKernelGGL(masked_copy_kernel<bf16_t>, dim3(blocks_for(numel)), dim3(256), 0, s,
+                           (const bf16_t*)dy, (const bf16_t*)y, (bf16_t*)dres, numel);
+    else
+        hipLaunchKernelGGL(masked_copy_kernel<float>, dim3(blocks_for(numel)), dim3(256), 0, s, (const float*)dy,
+                           (const float*)y, (float*)dres, numel);
+    return hipGetLastError();
+}
+
+hipError_t launch_l1_grad(int dtype, const void* y, const void* t, void* dy, long long numel, hipStream_t s) {
+    if (numel <= 0) return hipSuccess;
+    const float inv = (float)(1.0 / (double)numel);
+    if (dtype == 1)
+        hipLaunchKernelGGL(l1_grad_kernel<true>, dim3(blocks_for(numel)), dim3(256), 0, s, y, t, dy, numel, inv);
+    else
+        hipLaunchKernelGGL(l1_grad_kernel<false>, dim3(blocks_for(numel)), dim3(256), 0, s, y, t, dy, numel, inv);
+    return hipGetLastError();
+}
+
+hipError_t launch_maxpool(int dtype, const void* x, void* y, int N, int H, int W, int C, int k, int stride, int pad,
+                          hipStream_t s) {
+    const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
+    const long long total = (long long)N * Ho * Wo * C;
+    if (total <= 0) return hipSuccess;
+    if (dtype == 1)
+        hipLaunchKernelGGL(maxpool_kernel<true>, dim3(blocks_for(total)), dim3(256), 0, s, x, y, N, H, W, C, k, stride,
+                           pad, Ho, Wo);
+    else
+        hipLaunchKernelGGL(maxpool_kernel<false>, dim3(blocks_for(total)), dim3(256), 0, s, x, y, N, H, W, C, k,
+                           stride, pad, Ho, Wo);
+    return hipGetLastError();
+}
+
+}  // namespace sol
