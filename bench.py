@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Throughput of the fused conv + affine (+ residual) + ReLU blocks, forward and backward.
+
+One step = one pass of the whole path over one batch of synthetic input already resident in
+HBM: forward of every block of the workload, the L1-loss gradient, backward of every block
+(data gradient, weight gradient, affine-parameter gradients).  The default workload is the
+14x14 bottleneck (1x1 1024->256, 3x3 256->256, 1x1 256->1024 + identity shortcut + ReLU, N = 64,
+bf16 with fp32 accumulation), the configuration the throughput target is quoted on.
+
+Prints ONE JSON line.  `roofline` describes the dominant kernel (the bf16 MFMA implicit-GEMM
+kernel, timed on its largest launch of the step, the 3x3 forward convolution) with HIP events on
+the launch stream; `cpu_baseline` is the fp64 CPU checker timed on a bounded sample of the same
+workload on this host.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=3, choices=[2, 3, 5])
+    ap.add_argument("--batch", type=int, default=0, help="override N (0 = the workload's own)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-images", type=int, default=32)
+    return ap.parse_args()
+
+
+def cpu_baseline(wl_factory, images: int):
+    """The CPU checker, as it stands, on the first `images` images of the workload."""
+    import numpy as np
+    from oracle import oracle as orc
+    wl = wl_factory(images)
+    shp = wl.tensor_shapes()
+    t0 = time.perf_counter()
+    acts = {0: wl.x.astype(np.float64)}
+    for o in wl.conv_blocks():
+        p = wl.params[o.layer]
+        _, h, w = shp[o.inp]
+        d = orc.Desc(wl.n, h, w, o.c_in, o.c_out, o.k, o.k, o.stride, o.pad, o.relu)
+        acts[o.out] = orc.block_fwd(d, acts[o.inp], p["W"], p["scale"], p["shift"],
+                                    acts[o.res] if o.res is not None else None)
+    last = wl.conv_blocks()[-1].out
+    grads = {last: orc.l1_grad(acts[last], wl.target)}
+    for o in reversed(wl.conv_blocks()):
+        p = wl.params[o.layer]
+        _, h, w = shp[o.inp]
+        d = orc.Desc(wl.n, h, w, o.c_in, o.c_out, o.k, o.k, o.stride, o.pad, o.relu)
+        need_dx = not (o.inp == 0 and not wl.need_input_grad)
+        g = orc.block_bwd(d, grads[o.out], acts[o.inp], p["W"], acts[o.out], p["scale"], need_dx=need_dx,
+                          need_dres=o.res is not None)
+        if need_dx:
+            grads[o.inp] = g["dx"] if o.inp not in grads else grads[o.inp] + g["dx"]
+        if o.res is not None:
+            grads[o.res] = g["dres"] if o.res not in grads else grads[o.res] + g["dres"]
+    dt = time.perf_counter() - t0
+    return wl.flops_step() / dt / 1e12, dt, orc.num_threads()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only (this build has no multi-GPU path); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2205_10357_amd import binding as B
+    from paper_2205_10357_amd import runner, workloads
+
+    B.lib()
+    factories = {
+        2: lambda n: workloads.stem_bf16(n=n),
+        3: lambda n: workloads.bottleneck14_bf16(n=n),
+        5: lambda n: workloads.stage2_train_bf16(n=n),
+    }
+    default_n = {2: 32, 3: 64, 5: 128}[args.workload]
+    n = args.batch or default_n
+    wl = factories[args.workload](n)
+    torch.cuda.set_device(0)
+    seq = runner.Sequencer(wl, "cuda:0")
+    stream = torch.cuda.current_stream()
+
+    for _ in range(args.warmup):
+        seq.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        seq.step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = dt / args.steps * 1e3
+    flops = wl.flops_step()
+    value = flops / (ms * 1e-3) / 1e12
+
+    # ---- dominant kernel: the implicit-GEMM kernel on the largest forward launch of the step ----
+    shp = wl.tensor_shapes()
+    blocks = wl.conv_blocks()
+    big = max(blocks, key=lambda b: workloads.conv_flops(n, shp[b.inp][1], shp[b.inp][2], b))
+    kflops = workloads.conv_flops(n, shp[big.inp][1], shp[big.inp][2], big)
+    p = seq.params[big.layer]
+    reps = max(50, args.steps)
+
+    def launch():
+        B.sol_block_fwd(seq.desc[big.layer], seq.act[big.inp], p["W"], p["scale"], p["shift"],
+                        seq.act[big.res] if big.res is not None else None, seq.act[big.out], None, 0, stream)
+
+    for _ in range(10):
+        launch()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(reps):
+        launch()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    k_us = e0.elapsed_time(e1) / reps * 1e3
+    achieved = kflops / (k_us * 1e-6) / 1e12
+
+    out = {
+        "metric": "TFLOP/s fused conv+BN+ReLU fwd+bwd, ResNet-50 shapes bf16; % MFMA peak",
+        "value": round(value, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "global_batch": n, "blocks": len(blocks),
+                   "flop_per_step": flops, "pct_mfma_peak": round(100 * value / MFMA_BF16_PEAK_TFLOPS, 2)},
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "kernel": "igemm_bf16_kernel", "launch": f"{big.name} forward", "avg_us": round(k_us, 3)},
+    }
+    if not args.no_cpu_baseline:
+        images = min(args.cpu_sample_images, n)
+        v, secs, cores = cpu_baseline(factories[args.workload], images)
+        out["cpu_baseline"] = {"value": round(v, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+                               "sample": f"first {images} of {n} images, forward + L1 gradient + backward, "
+                                         f"{secs:.1f} s"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

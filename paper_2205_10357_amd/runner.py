@@ -1,0 +1,185 @@
+"""Static layer-list sequencing of fused blocks on one GPU.
+
+The paper's compiled network is a single library holding the whole execution pipeline
+with a static schedule (section "SOL architecture", last paragraph before the SDK note;
+section on memory consumption).  Here the schedule is the op list of a
+``workloads.Workload``: one ``sol_block_fwd`` per convolution block in order, the loss
+gradient, then one ``sol_block_bwd`` per block in reverse order.  torch is used only to
+own device buffers and the stream; every arithmetic step runs in the library's kernels.
+
+Shortcut gradients never get a pass of their own:
+  * identity shortcut: the block input's gradient is dx(conv1) + dy_tail * [y_tail > 0]; the
+    second term is added in conv1's data-gradient epilogue (``dx_addend`` = dy_tail gated by
+    ``dx_addend_mask`` = y_tail);
+  * projection shortcut: the projection has no ReLU of its own, so its backward is called
+    with the tail block's y as mask source, which makes its g equal to the tail's g.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+from .workloads import ConvBlock, Workload, out_size
+
+
+def nchw_to_nhwc(a: np.ndarray) -> np.ndarray:
+    return np.ascontiguousarray(np.transpose(a, (0, 2, 3, 1)))
+
+
+def nhwc_to_nchw(a: np.ndarray) -> np.ndarray:
+    return np.ascontiguousarray(np.transpose(a, (0, 3, 1, 2)))
+
+
+def oihw_to_krsc(w: np.ndarray) -> np.ndarray:
+    return np.ascontiguousarray(np.transpose(w, (0, 2, 3, 1)))
+
+
+def krsc_to_oihw(w: np.ndarray) -> np.ndarray:
+    return np.ascontiguousarray(np.transpose(w, (0, 3, 1, 2)))
+
+
+def upload(a: np.ndarray, dtype: torch.dtype, device) -> torch.Tensor:
+    """float32 host values (already on the storage grid of `dtype`) -> device tensor."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device=device, dtype=dtype)
+
+
+def download(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(device="cpu", dtype=torch.float64).numpy()
+
+
+class Sequencer:
+    """Device buffers + launch order for one workload."""
+
+    def __init__(self, wl: Workload, device="cuda:0"):
+        self.wl = wl
+        self.device = torch.device(device)
+        self.bf16 = wl.dtype == "bf16"
+        self.sol_dtype = B.SOL_BF16 if self.bf16 else B.SOL_F32
+        self.tdtype = torch.bfloat16 if self.bf16 else torch.float32
+        self.shapes = wl.tensor_shapes()              # tensor id -> (C, H, W)
+        self.ops = wl.ops
+        n = wl.n
+        self.act: Dict[int, torch.Tensor] = {}        # NHWC activations
+        self.act[0] = upload(nchw_to_nhwc(wl.x), self.tdtype, self.device)
+        for o in self.ops:
+            c, h, w = self.shapes[o.out]
+            self.act[o.out] = torch.empty((n, h, w, c), dtype=self.tdtype, device=self.device)
+        self.params: Dict[int, Dict[str, torch.Tensor]] = {}
+        self.desc: Dict[int, B.BlockDesc] = {}
+        ws_bytes = 0
+        for o in self.ops:
+            if o.op != "conv":
+                continue
+            p = wl.params[o.layer]
+            self.params[o.layer] = {
+                "W": upload(oihw_to_krsc(p["W"]), self.tdtype, self.device),
+                "scale": upload(p["scale"], torch.float32, self.device),
+                "shift": upload(p["shift"], torch.float32, self.device),
+            }
+            _, h, w = self.shapes[o.inp]
+            d = B.BlockDesc(n, h, w, o.c_in, o.c_out, o.k, o.k, o.stride, o.pad, self.sol_dtype,
+                            B.SOL_RELU if o.relu else 0)
+            self.desc[o.layer] = d
+            if wl.train:
+                ws_bytes = max(ws_bytes, B.sol_block_workspace_bytes(d, B.SOL_PASS_BWD),
+                               B.sol_block_workspace_bytes(
+                                   B.BlockDesc(n, h, w, o.c_in, o.c_out, o.k, o.k, o.stride, o.pad,
+                                               self.sol_dtype, B.SOL_RELU), B.SOL_PASS_BWD))
+        self.ws = torch.empty((max(ws_bytes, 256),), dtype=torch.uint8, device=self.device)
+        self.grads: Dict[int, Dict[str, torch.Tensor]] = {}
+        self.dact: Dict[int, torch.Tensor] = {}
+        self.target: Optional[torch.Tensor] = None
+        if wl.train:
+            self.target = upload(nchw_to_nhwc(wl.target), self.tdtype, self.device)
+            for o in self.ops:
+                if o.op != "conv":
+                    continue
+                p = self.params[o.layer]
+                self.grads[o.layer] = {
+                    "dW": torch.empty(p["W"].shape, dtype=torch.float32, device=self.device),
+                    "dscale": torch.empty(o.c_out, dtype=torch.float32, device=self.device),
+                    "dshift": torch.empty(o.c_out, dtype=torch.float32, device=self.device),
+                }
+            # one gradient buffer per activation that some backward call reads or writes densely
+            for tid, (c, h, w) in self.shapes.items():
+                if tid == 0 and not wl.need_input_grad:
+                    continue
+                self.dact[tid] = torch.empty((n, h, w, c), dtype=self.tdtype, device=self.device)
+            self._plan_backward()
+
+    # ------------------------------------------------------------------ forward
+    def forward(self, stream=None) -> torch.Tensor:
+        for o in self.ops:
+            if o.op == "conv":
+                p = self.params[o.layer]
+                B.sol_block_fwd(self.desc[o.layer], self.act[o.inp], p["W"], p["scale"], p["shift"],
+                                self.act[o.res] if o.res is not None else None, self.act[o.out],
+                                None, 0, stream)
+            else:
+                c, h, w = self.shapes[o.inp]
+                B.sol_maxpool_fwd(self.sol_dtype, self.act[o.inp], self.act[o.out], self.wl.n, h, w, c,
+                                  o.k, o.stride, o.pad, stream)
+        return self.act[self.ops[-1].out]
+
+    # ---------------------------------------------------------------- loss grad
+    def loss_grad(self, stream=None) -> torch.Tensor:
+        last = self.ops[-1].out
+        y = self.act[last]
+        B.sol_l1_loss_grad(self.sol_dtype, y, self.target, self.dact[last], y.numel(), stream)
+        return self.dact[last]
+
+    # ----------------------------------------------------------------- backward
+    def _plan_backward(self) -> None:
+        """Resolve, once, the arguments of every backward call (reverse op order)."""
+        state: Dict[int, object] = {self.ops[-1].out: "dense"}
+        calls: List[dict] = []
+        for o in reversed(self.ops):
+            if o.op != "conv":
+                raise NotImplementedError("backward through the max-pool is not part of any training workload")
+            st = state.get(o.out)
+            if st is None:
+                raise RuntimeError(f"no gradient reaches {o.name}")
+            d = self.desc[o.layer]
+            if st == "dense":
+                dy, ymask, desc = self.dact[o.out], self.act[o.out], d
+            else:                                   # ("masked", tail op): gradient = dy_tail * [y_tail > 0]
+                tail: ConvBlock = st[1]
+                if o.relu:
+                    raise NotImplementedError("masked shortcut gradient into a block with its own ReLU")
+                dy, ymask = self.dact[tail.out], self.act[tail.out]
+                desc = B.BlockDesc(d.N, d.H, d.W, d.C_in, d.C_out, d.KH, d.KW, d.stride, d.pad, d.dtype,
+                                   d.flags | B.SOL_RELU)
+            call = dict(op=o, desc=desc, dy=dy, y=ymask, dx=None, addend=None, addend_mask=None)
+            if o.res is not None:
+                if state.get(o.res) is not None:
+                    raise NotImplementedError("shortcut gradient arriving after another gradient")
+                state[o.res] = ("masked", o)
+            want_dx = not (o.inp == 0 and not self.wl.need_input_grad)
+            if want_dx:
+                prev = state.get(o.inp)
+                call["dx"] = self.dact[o.inp]
+                if prev == "dense":
+                    call["addend"] = self.dact[o.inp]
+                elif prev is not None:
+                    tail = prev[1]
+                    call["addend"], call["addend_mask"] = self.dact[tail.out], self.act[tail.out]
+                state[o.inp] = "dense"
+            calls.append(call)
+        self._bwd_calls = calls
+
+    def backward(self, stream=None) -> None:
+        for c in self._bwd_calls:
+            o = c["op"]
+            p, g = self.params[o.layer], self.grads[o.layer]
+            B.sol_block_bwd(c["desc"], c["dy"], self.act[o.inp], p["W"], c["y"], c["dx"], g["dW"], g["dscale"],
+                            g["dshift"], p["scale"], None, c["addend"], c["addend_mask"], self.ws, None, stream)
+
+    def step(self, stream=None) -> None:
+        """One pass of the whole path: forward, and for training the loss gradient and backward."""
+        self.forward(stream)
+        if self.wl.train:
+            self.loss_grad(stream)
+            self.backward(stream)

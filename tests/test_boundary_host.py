@@ -1,0 +1,95 @@
+"""Host-only checks of the C-ABI library: it loads, exports what the header declares, and rejects
+bad arguments before touching the device (no compute call is made here)."""
+import os
+import re
+
+import pytest
+
+from paper_2205_10357_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000      # 16-byte aligned, never dereferenced: validation fails first
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sol_block.h")).read()
+    return re.findall(r"SOL_API\s+[\w\s\*]+?\b(sol_\w+)\s*\(", text)
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert set(names) == set(B.EXPORTS) and len(names) == 6
+    lib = B.lib()
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings():
+    assert B.sol_status_string(0) == "ok"
+    for s in range(-6, 0):
+        assert B.sol_status_string(s) not in ("ok", "unknown status")
+    assert B.sol_status_string(-99) == "unknown status"
+
+
+def desc(**kw):
+    base = dict(N=2, H=8, W=8, C_in=16, C_out=32, KH=3, KW=3, stride=1, pad=1, dtype=B.SOL_BF16, flags=B.SOL_RELU)
+    base.update(kw)
+    return B.BlockDesc(**base)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(N=0), -2), (dict(C_in=-1), -2), (dict(stride=0), -2), (dict(pad=-1), -2),
+    (dict(H=1, W=1, KH=3, KW=3, pad=0), -2),                 # empty output
+    (dict(dtype=7), -4), (dict(flags=8), -4),
+    (dict(N=70000, H=224, W=224, C_in=64), -4),              # beyond 2^31-1 elements
+])
+def test_descriptor_validation(kw, status):
+    d = desc(**kw)
+    assert B.sol_block_fwd(d, FAKE, FAKE, FAKE, FAKE, None, FAKE, None, 0, stream=0, check=False) == status
+    assert B.sol_block_bwd(d, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None, FAKE, 1 << 40,
+                           stream=0, check=False) == status
+    assert B.sol_block_workspace_bytes(d, B.SOL_PASS_BWD) == 0
+
+
+def test_pointer_validation():
+    d = desc()
+    assert B.sol_block_fwd(d, None, FAKE, FAKE, FAKE, None, FAKE, None, 0, stream=0, check=False) == -1
+    assert B.sol_block_fwd(d, FAKE, FAKE, FAKE, None, None, FAKE, None, 0, stream=0, check=False) == -1
+    assert B.sol_block_fwd(d, FAKE + 8, FAKE, FAKE, FAKE, None, FAKE, None, 0, stream=0, check=False) == -3
+    assert B.sol_block_fwd(d, FAKE, FAKE, FAKE, FAKE, FAKE + 2, FAKE, None, 0, stream=0, check=False) == -3
+    args = [FAKE] * 9
+    assert B.sol_block_bwd(d, None, *args[1:], None, None, None, FAKE, 1 << 40, stream=0, check=False) == -1
+    # ReLU block needs y for the mask; a block without ReLU does not
+    assert B.sol_block_bwd(d, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None, FAKE, 1 << 40,
+                           stream=0, check=False) == -1
+    # addend mask without addend
+    assert B.sol_block_bwd(d, *args, None, None, FAKE, FAKE, 1 << 40, stream=0, check=False) == -1
+    # workspace missing / too small
+    need = B.sol_block_workspace_bytes(d, B.SOL_PASS_BWD)
+    assert need > 0
+    assert B.sol_block_bwd(d, *args, None, None, None, None, 0, stream=0, check=False) == -5
+    assert B.sol_block_bwd(d, *args, None, None, None, FAKE, need - 1, stream=0, check=False) == -5
+    # bf16 data gradient supports stride <= 2
+    d3 = desc(stride=3)
+    assert B.sol_block_bwd(d3, *args, None, None, None, FAKE, 1 << 40, stream=0, check=False) == -4
+    with pytest.raises(B.SolError):
+        B.sol_block_fwd(d, None, FAKE, FAKE, FAKE, None, FAKE, None, 0, stream=0)
+
+
+def test_workspace_sizes():
+    assert B.sol_block_workspace_bytes(desc(), B.SOL_PASS_FWD) == 0
+    d = desc(N=64, H=14, W=14, C_in=256, C_out=256)
+    need = B.sol_block_workspace_bytes(d, B.SOL_PASS_BWD)
+    k = 9 * 256
+    assert need >= 256 * k * 2 + 256 * k * 4           # packed weights + at least one fp32 partial
+    assert need < 256 << 20
+    f32 = desc(dtype=B.SOL_F32)
+    assert B.sol_block_workspace_bytes(f32, B.SOL_PASS_BWD) >= 32 * 9 * 16 * 4 + 32 * 4
+
+
+def test_glue_validation():
+    assert B.sol_l1_loss_grad(B.SOL_BF16, FAKE, FAKE, FAKE, 0, stream=0, check=False) == -2
+    assert B.sol_l1_loss_grad(5, FAKE, FAKE, FAKE, 16, stream=0, check=False) == -4
+    assert B.sol_l1_loss_grad(B.SOL_F32, None, FAKE, FAKE, 16, stream=0, check=False) == -1
+    assert B.sol_maxpool_fwd(B.SOL_BF16, FAKE, FAKE, 1, 8, 8, 8, 3, 2, 3, stream=0, check=False) == -2
+    assert B.sol_maxpool_fwd(B.SOL_BF16, FAKE, None, 1, 8, 8, 8, 3, 2, 1, stream=0, check=False) == -1

@@ -1,0 +1,162 @@
+"""GPU parity: the HIP path, called through the C-ABI, against the CPU checker on the same
+seeded inputs.  Tolerances: max relative L2 error 1e-5 (fp32) / 1e-2 (bf16) per output tensor,
+ReLU mask and masked gradients bit-exact."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from oracle import oracle as orc                              # noqa: E402
+from paper_2205_10357_amd import binding as B                 # noqa: E402
+from paper_2205_10357_amd import workloads as wl              # noqa: E402
+from tests import parity_util as pu                           # noqa: E402
+
+
+def show(name, errs):
+    print(f"[parity] {name}: " + " ".join(f"{k}={v:.3g}" if isinstance(v, float) else f"{k}={v}" for k, v in errs.items()),
+          flush=True)
+
+
+# ------------------------------------------------------------------ workload 1 (fp32)
+def test_single_block_fp32_matches_checker():
+    w = wl.single_block_f32()
+    p = w.params[0]
+    case = dict(d=orc.Desc(1, 16, 16, 16, 16, 3, 3, 1, 1, True), bf16=False, x=w.x, w=p["W"], scale=p["scale"],
+                shift=p["shift"], res=None, t=w.target)
+    got = pu.gpu_block(case)
+    errs = pu.check_block(case, got)
+    show("single_block_f32", errs)
+    assert errs["mask_band"] == 0        # no pre-activation of this seed sits inside the rounding band
+
+
+@pytest.mark.parametrize("shape", [
+    dict(N=2, H=9, W=7, C_in=5, C_out=6, K=3, stride=1, pad=1, res=True),
+    dict(N=1, H=11, W=10, C_in=3, C_out=4, K=7, stride=2, pad=3),
+    dict(N=2, H=8, W=8, C_in=8, C_out=4, K=1, stride=2, pad=0, relu=False),
+])
+def test_fp32_other_shapes(shape):
+    case = pu.make_case(31, bf16=False, **shape)
+    got = pu.gpu_block(case, want_dres=True)
+    show(f"f32 {shape}", pu.check_block(case, got))
+
+
+# --------------------------------------------------- bf16: the distinct ResNet-50 layer shapes
+RESNET_SHAPES = [  # (name, C_in, C_out, H, k, stride, pad, residual)
+    ("stem", 3, 64, 224, 7, 2, 3, False),
+    ("s1.conv1a", 64, 64, 56, 1, 1, 0, False),
+    ("s1.conv2", 64, 64, 56, 3, 1, 1, False),
+    ("s1.proj", 64, 256, 56, 1, 1, 0, False),
+    ("s1.conv3", 64, 256, 56, 1, 1, 0, True),
+    ("s1.conv1b", 256, 64, 56, 1, 1, 0, False),
+    ("s2.conv1a", 256, 128, 56, 1, 1, 0, False),
+    ("s2.conv2a", 128, 128, 56, 3, 2, 1, False),
+    ("s2.proj", 256, 512, 56, 1, 2, 0, False),
+    ("s2.conv3", 128, 512, 28, 1, 1, 0, True),
+    ("s2.conv1b", 512, 128, 28, 1, 1, 0, False),
+    ("s2.conv2b", 128, 128, 28, 3, 1, 1, False),
+    ("s3.conv1a", 512, 256, 28, 1, 1, 0, False),
+    ("s3.conv2a", 256, 256, 28, 3, 2, 1, False),
+    ("s3.proj", 512, 1024, 28, 1, 2, 0, False),
+    ("s3.conv3", 256, 1024, 14, 1, 1, 0, True),
+    ("s3.conv1b", 1024, 256, 14, 1, 1, 0, False),
+    ("s3.conv2b", 256, 256, 14, 3, 1, 1, False),
+    ("s4.conv1a", 1024, 512, 14, 1, 1, 0, False),
+    ("s4.conv2a", 512, 512, 14, 3, 2, 1, False),
+    ("s4.proj", 1024, 2048, 14, 1, 2, 0, False),
+    ("s4.conv3", 512, 2048, 7, 1, 1, 0, True),
+    ("s4.conv1b", 2048, 512, 7, 1, 1, 0, False),
+    ("s4.conv2b", 512, 512, 7, 3, 1, 1, False),
+]
+
+
+@pytest.mark.parametrize("spec", RESNET_SHAPES, ids=[s[0] for s in RESNET_SHAPES])
+def test_bf16_resnet50_layer_shapes(spec):
+    name, c_in, c_out, h, k, stride, pad, res = spec
+    n = 1 if h >= 56 else (2 if h >= 14 else 5)          # several pixel tiles and a ragged last one
+    relu = "proj" not in name
+    case = pu.make_case(100 + len(name), n, h, h, c_in, c_out, k, stride, pad, relu=relu, res=res)
+    got = pu.gpu_block(case, need_dx=(name != "stem"))
+    show(name, pu.check_block(case, got, need_dx=(name != "stem")))
+
+
+@pytest.mark.parametrize("shape", [
+    dict(N=1, H=1, W=1, C_in=8, C_out=8, K=3, stride=1, pad=1),               # single pixel, only the centre tap
+    dict(N=3, H=5, W=7, C_in=16, C_out=24, K=3, stride=1, pad=1, res=True),   # fewer rows than one tile
+    dict(N=1, H=13, W=11, C_in=12, C_out=20, K=3, stride=1, pad=1),           # channels not a multiple of 8
+    dict(N=2, H=9, W=11, C_in=24, C_out=16, K=3, stride=2, pad=1),            # odd sizes under stride 2
+    dict(N=2, H=7, W=9, C_in=16, C_out=40, K=1, stride=2, pad=0, relu=False), # 1x1/s2: 3 of 4 pixel classes see no tap
+    dict(N=1, H=12, W=12, C_in=3, C_out=8, K=7, stride=2, pad=3),             # stem-like with a data gradient
+    dict(N=1, H=33, W=31, C_in=64, C_out=136, K=3, stride=1, pad=1),          # ragged in pixels and channels
+    dict(N=2, H=6, W=6, C_in=8, C_out=8, K=5, stride=1, pad=2),               # 5x5
+    dict(N=1, H=8, W=8, C_in=16, C_out=16, K=3, stride=1, pad=0),             # no padding
+])
+def test_bf16_edge_shapes(shape):
+    case = pu.make_case(7, **shape)
+    got = pu.gpu_block(case, want_dres=True)
+    show(f"edge {shape}", pu.check_block(case, got))
+
+
+@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+def test_bf16_every_tile_shape(tile, monkeypatch):
+    monkeypatch.setenv("SOL_IGEMM_TILE", str(tile))
+    case = pu.make_case(9, 2, 19, 17, 32, 136, 3, 1, 1, res=True)
+    got = pu.gpu_block(case)
+    show(f"tile{tile}", pu.check_block(case, got))
+
+
+@pytest.mark.parametrize("splits", [1, 3, 50])
+def test_bf16_wgrad_split_counts(splits, monkeypatch):
+    monkeypatch.setenv("SOL_WGRAD_SPLITS", str(splits))
+    case = pu.make_case(10, 2, 21, 19, 32, 40, 3, 1, 1)
+    got = pu.gpu_block(case)
+    show(f"splits{splits}", pu.check_block(case, got))
+
+
+def test_bf16_addend_mask_and_accumulate():
+    case = pu.make_case(11, 2, 10, 9, 16, 24, 3, 1, 1, res=True)
+    r = np.random.default_rng(12)
+    ad = wl.snap_to_bf16(r.standard_normal(case["x"].shape).astype(np.float32))
+    am = wl.snap_to_bf16(np.maximum(r.standard_normal(case["x"].shape), 0).astype(np.float32))
+    got = pu.gpu_block(case, addend=ad, addend_mask=am, want_dres=True)
+    show("addend+mask", pu.check_block(case, got, addend=ad, addend_mask=am))
+    got = pu.gpu_block(case, addend=ad)
+    show("addend", pu.check_block(case, got, addend=ad))
+    # accumulate flag: results are added to what the buffers held
+    base = pu.gpu_block(case)
+    init = r.standard_normal(case["w"].shape).astype(np.float32)
+    acc = pu.gpu_block(case, accumulate=True, dw_init=init)
+    np.testing.assert_allclose(acc["dW"], base["dW"] + init, rtol=1e-6, atol=1e-7)
+    np.testing.assert_allclose(acc["dscale"], base["dscale"] + 1.0, rtol=1e-6, atol=1e-7)
+    np.testing.assert_allclose(acc["dshift"], base["dshift"] - 2.0, rtol=1e-6, atol=1e-7)
+
+
+def test_runs_are_bitwise_reproducible():
+    case = pu.make_case(13, 2, 28, 28, 64, 128, 3, 1, 1, res=True)
+    a, b = pu.gpu_block(case), pu.gpu_block(case)
+    for k in ("y", "dx", "dW", "dscale", "dshift"):
+        assert np.array_equal(a[k], b[k]), k
+
+
+def test_masked_gradient_is_exactly_zero_where_y_is_zero():
+    case = pu.make_case(14, 2, 14, 14, 32, 64, 1, 1, 0)
+    got = pu.gpu_block(case, want_dres=True)
+    assert np.all(got["dres"][got["y"] == 0] == 0)
+    assert np.array_equal(got["dres"][got["y"] > 0], got["dy"][got["y"] > 0])
+    # weights = 0 and shift < 0: every output is 0, so every gradient must be exactly 0
+    case["w"] = np.zeros_like(case["w"])
+    case["shift"] = -np.abs(case["shift"]) - 0.1
+    got = pu.gpu_block(case)
+    assert np.all(got["y"] == 0) and np.all(got["dx"] == 0) and np.all(got["dW"] == 0)
+    assert np.all(got["dscale"] == 0) and np.all(got["dshift"] == 0)
+
+
+def test_error_codes_on_device_pointers():
+    d = B.BlockDesc(1, 8, 8, 8, 8, 3, 3, 1, 1, B.SOL_BF16, B.SOL_RELU)
+    t = torch.zeros(4096, dtype=torch.bfloat16, device="cuda")
+    f = torch.zeros(64, dtype=torch.float32, device="cuda")
+    assert B.sol_block_fwd(d, t, t, f, f, None, None, None, 0, check=False) == -1          # y NULL
+    assert B.sol_block_fwd(d, t.data_ptr() + 2, t, f, f, None, t, None, 0, check=False) == -3   # misaligned
+    ws = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    assert B.sol_block_bwd(d, t, t, t, t, t, f, f, f, f, None, None, None, ws, 16, check=False) == -5
