@@ -90,19 +90,26 @@ SOL_API int sol_block_fwd(const sol_block_desc* desc, const void* x, const void*
  *   dx[n,hi,wi,ci]  = sum_{kh,kw,co} g[n,ho,wo,co] * scale[co] * W[co,kh,kw,ci]   (+ addend)
  *   dW[co,kh,kw,ci] = scale[co] * sum_{n,ho,wo} g[n,ho,wo,co] * x[n,hi,wi,ci]
  *   dshift[co]      = sum g[.,co]          dscale[co] = sum g[.,co] * conv(x,W)[.,co]
- * Nullable: dx (skips the data gradient altogether), dres, dx_addend, dx_addend_mask.
+ * Nullable: dx (skips the data gradient altogether), dres, dx_addend, dx_addend_mask, dx_mask.
  *   dres            out, [N][Ho][Wo][C_out]: g itself (the gradient of the residual input).
  *   dx_addend       in,  [N][H][W][C_in]: added to dx in the epilogue (shortcut gradients).
  *   dx_addend_mask  in,  same shape as dx_addend: when given, only elements whose mask value
  *                   is > 0 are added (lets a shortcut pass dy of the tail block together with
  *                   that block's y instead of materialising its g).
+ *   dx_mask         in,  same shape as dx: when given, dx is stored as 0 wherever the mask value
+ *                   is <= 0 (applied after the addend).  Passing the block input -- the stored
+ *                   output of the ReLU block that produced it -- hands the upstream block a
+ *                   gradient that is already masked, so that block can be called without
+ *                   SOL_RELU and without its y: the mask costs one read here instead of one read
+ *                   in each of the upstream block's two gradient kernels.
  * scale is required (dx and dW carry it); shift never enters a gradient.
  * Results do not depend on run or launch order (no floating-point atomics).
  */
 SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void* x, const void* W,
                   const void* y, void* dx, float* dW, float* dscale, float* dshift,
                   const float* scale, void* dres, const void* dx_addend,
-                  const void* dx_addend_mask, void* ws, size_t ws_bytes, void* hip_stream);
+                  const void* dx_addend_mask, const void* dx_mask, void* ws, size_t ws_bytes,
+                  void* hip_stream);
 
 /* Bytes of caller-provided scratch the given pass needs for this descriptor (0 if the
  * descriptor is invalid: the pass itself then reports the error). */
@@ -117,9 +124,10 @@ SOL_API const char* sol_status_string(int status);
  * training step can run without any framework kernel.  Same pointer / stream rules.
  */
 
-/* dy = sign(y - t) / numel (sign(0) = 0): gradient of the mean absolute error. */
+/* dy = sign(y - t) / numel (sign(0) = 0): gradient of the mean absolute error.  With mask_by_y != 0
+ * the result is additionally 0 wherever y <= 0, i.e. already masked by the ReLU that produced y. */
 SOL_API int sol_l1_loss_grad(int32_t dtype, const void* y, const void* t, void* dy, int64_t numel,
-                     void* hip_stream);
+                     int32_t mask_by_y, void* hip_stream);
 
 /* Max-pool k x k / stride / pad over NHWC (padding never wins). */
 SOL_API int sol_maxpool_fwd(int32_t dtype, const void* x, void* y, int32_t N, int32_t H, int32_t W,

@@ -73,14 +73,14 @@ def lib():
         l.sol_block_fwd.restype = C.c_int
         l.sol_block_fwd.argtypes = [C.POINTER(_CDesc), vp, vp, fp, fp, vp, vp, vp, C.c_size_t, vp]
         l.sol_block_bwd.restype = C.c_int
-        l.sol_block_bwd.argtypes = [C.POINTER(_CDesc), vp, vp, vp, vp, vp, fp, fp, fp, fp, vp, vp, vp, vp,
+        l.sol_block_bwd.argtypes = [C.POINTER(_CDesc), vp, vp, vp, vp, vp, fp, fp, fp, fp, vp, vp, vp, vp, vp,
                                     C.c_size_t, vp]
         l.sol_block_workspace_bytes.restype = C.c_size_t
         l.sol_block_workspace_bytes.argtypes = [C.POINTER(_CDesc), C.c_int]
         l.sol_status_string.restype = C.c_char_p
         l.sol_status_string.argtypes = [C.c_int]
         l.sol_l1_loss_grad.restype = C.c_int
-        l.sol_l1_loss_grad.argtypes = [C.c_int32, vp, vp, vp, C.c_int64, vp]
+        l.sol_l1_loss_grad.argtypes = [C.c_int32, vp, vp, vp, C.c_int64, C.c_int32, vp]
         l.sol_maxpool_fwd.restype = C.c_int
         l.sol_maxpool_fwd.argtypes = [C.c_int32, vp, vp] + [C.c_int32] * 7 + [vp]
         _lib = l
@@ -137,20 +137,22 @@ def sol_block_fwd(desc, x, W, scale, shift, residual, y, ws=None, ws_bytes: Opti
 
 
 def sol_block_bwd(desc, dy, x, W, y, dx, dW, dscale, dshift, scale, dres=None, dx_addend=None,
-                  dx_addend_mask=None, ws=None, ws_bytes: Optional[int] = None, stream=None,
+                  dx_addend_mask=None, dx_mask=None, ws=None, ws_bytes: Optional[int] = None, stream=None,
                   check: bool = True) -> int:
     d = _cdesc(desc)
     nb = _nbytes(ws) if ws_bytes is None else ws_bytes
     st = lib().sol_block_bwd(C.byref(d), _ptr(dy), _ptr(x), _ptr(W), _ptr(y), _ptr(dx), _ptr(dW), _ptr(dscale),
                              _ptr(dshift), _ptr(scale), _ptr(dres), _ptr(dx_addend), _ptr(dx_addend_mask),
-                             _ptr(ws), nb, _stream(stream))
+                             _ptr(dx_mask), _ptr(ws), nb, _stream(stream))
     if check and st != 0:
         raise SolError(st, "sol_block_bwd")
     return st
 
 
-def sol_l1_loss_grad(dtype: int, y, t, dy, numel: int, stream=None, check: bool = True) -> int:
-    st = lib().sol_l1_loss_grad(int(dtype), _ptr(y), _ptr(t), _ptr(dy), int(numel), _stream(stream))
+def sol_l1_loss_grad(dtype: int, y, t, dy, numel: int, mask_by_y: bool = False, stream=None,
+                     check: bool = True) -> int:
+    st = lib().sol_l1_loss_grad(int(dtype), _ptr(y), _ptr(t), _ptr(dy), int(numel), int(bool(mask_by_y)),
+                                _stream(stream))
     if check and st != 0:
         raise SolError(st, "sol_l1_loss_grad")
     return st

@@ -40,6 +40,10 @@ int check_desc(const sol_block_desc* d, Geometry* g) {
     return SOL_OK;
 }
 
+// hipGetLastError() reports the last error of ANY earlier HIP call on this thread (the caller's
+// framework included); drop it so that the check after our launches sees only our own.
+inline void clear_stale_error() { (void)hipGetLastError(); }
+
 int env_int(const char* name, int fallback) {
     const char* v = getenv(name);
     if (!v || !*v) return fallback;
@@ -64,6 +68,59 @@ int pick_igemm_tile(const long long* class_rows, int ncls, int Nc) {
         if (tiles >= 192) return order[i];
     }
     return order[n - 1];
+}
+
+// Fills tile-dependent fields of the launch (tile counts, class offsets) and launches either the
+// pipelined kernel (source channels % 64 == 0, output channels % 8 == 0, no mask on the gathered
+// operand) or the general one.  SOL_IGEMM_FAST=0 forces the general kernel; SOL_FAST_TILE /
+// SOL_FAST_STAGES override the pipelined kernel's tile and ring depth (tuning experiments).
+int run_igemm(IgemmParams& p, const long long* rows, bool mask, hipStream_t stream) {
+    const bool fast_ok = !mask && (p.Cs % 64) == 0 && (p.Nc % 8) == 0 && env_int("SOL_IGEMM_FAST", 1) != 0;
+    int bp, bc, tile = 0, stages = 0;
+    if (fast_ok) {
+        long long slices = 0;
+        for (int c = 0; c < p.ncls; ++c) {
+            const long long s = (long long)p.cls[c].Th * p.cls[c].Tw * (p.Cs / 64);
+            if (s > slices) slices = s;
+        }
+        tile = env_int("SOL_FAST_TILE", -1);
+        if (tile < 0 || tile > 3) {
+            // 128 x 128 unless that leaves most compute units idle or the GEMM is narrow
+            long long t128 = 0;
+            for (int c = 0; c < p.ncls; ++c) t128 += (rows[c] + 127) / 128;
+            t128 *= (p.Nc + 127) / 128;
+            tile = p.Nc <= 64 ? 1 : (t128 >= 160 ? 0 : 1);
+            long long t = 0;
+            igemm_fast_tile_shape(tile, &bp, &bc);
+            for (int c = 0; c < p.ncls; ++c) t += (rows[c] + bp - 1) / bp;
+            t *= (p.Nc + bc - 1) / bc;
+            if (t < 160) tile = 2;
+        }
+        stages = env_int("SOL_FAST_STAGES", 0);
+        if (stages < 2 || stages > 4) stages = slices <= 4 ? 2 : (slices <= 8 ? 3 : 4);
+        if (tile == 3 && stages > 3) stages = 3;
+        igemm_fast_tile_shape(tile, &bp, &bc);
+    } else {
+        tile = pick_igemm_tile(rows, p.ncls, p.Nc);
+        igemm_tile_shape(tile, &bp, &bc);
+    }
+    p.tiles_c = (p.Nc + bc - 1) / bc;
+    int tiles_p = 0;
+    for (int c = 0; c < p.ncls; ++c) {
+        RowClass& rc = p.cls[c];
+        const bool lin_src = rc.Th == 1 && rc.Tw == 1 && rc.h_mul == 1 && rc.w_mul == 1 && rc.h_off == 0 &&
+                             rc.w_off == 0 && rc.Rh == p.Hs && rc.Rw == p.Ws;
+        const bool lin_out = rc.oh_mul == 1 && rc.ow_mul == 1 && rc.oh_off == 0 && rc.ow_off == 0 &&
+                             rc.Rh == p.Hout && rc.Rw == p.Wout;
+        rc.linear = (lin_src ? 1 : 0) | (lin_out ? 2 : 0);
+        p.cls[c].tile_begin = tiles_p;
+        tiles_p += (int)((rows[c] + bp - 1) / bp);
+    }
+    p.total_tiles = tiles_p * p.tiles_c;
+    hipError_t e;
+    if (fast_ok) e = launch_igemm_fast(p, tile, stages, stream);
+    else e = launch_igemm(p, tile, (p.Cs % 8) == 0, mask, stream);
+    return e == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
 }
 
 struct BwdPlan {
@@ -141,17 +198,11 @@ int fwd_bf16(const sol_block_desc* d, const Geometry& g, const void* x, const vo
     c.tile_begin = 0;
     c.b_off = 0;
     const long long rows[1] = {g.M};
-    const int tile = pick_igemm_tile(rows, 1, d->C_out);
-    int bp, bc;
-    igemm_tile_shape(tile, &bp, &bc);
-    p.tiles_c = (d->C_out + bc - 1) / bc;
-    p.total_tiles = (int)((g.M + bp - 1) / bp) * p.tiles_c;
-    const bool vec = (d->C_in % 8) == 0;
-    return launch_igemm(p, tile, vec, false, stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
+    return run_igemm(p, rows, false, stream);
 }
 
 int dgrad_bf16(const sol_block_desc* d, const Geometry& g, const void* dy, const void* y, const bf16_t* wpack,
-               void* dx, const void* addend, const void* addend_mask, hipStream_t stream) {
+               void* dx, const void* addend, const void* addend_mask, const void* dx_mask, hipStream_t stream) {
     const int s = d->stride;
     IgemmParams p{};
     const bool relu = (d->flags & SOL_RELU) != 0;
@@ -163,6 +214,7 @@ int dgrad_bf16(const sol_block_desc* d, const Geometry& g, const void* dy, const
     p.shift = nullptr;
     p.addend = (const bf16_t*)addend;
     p.addend_mask = (const bf16_t*)addend_mask;
+    p.out_mask = (const bf16_t*)dx_mask;
     p.Hs = g.Ho;
     p.Ws = g.Wo;
     p.Cs = d->C_out;
@@ -202,18 +254,7 @@ int dgrad_bf16(const sol_block_desc* d, const Geometry& g, const void* dy, const
             ++nc;
         }
     p.ncls = nc;
-    const int tile = pick_igemm_tile(rows, nc, d->C_in);
-    int bp, bc;
-    igemm_tile_shape(tile, &bp, &bc);
-    p.tiles_c = (d->C_in + bc - 1) / bc;
-    int tiles_p = 0;
-    for (int c = 0; c < nc; ++c) {
-        p.cls[c].tile_begin = tiles_p;
-        tiles_p += (int)((rows[c] + bp - 1) / bp);
-    }
-    p.total_tiles = tiles_p * p.tiles_c;
-    const bool vec = (d->C_out % 8) == 0;
-    return launch_igemm(p, tile, vec, relu, stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
+    return run_igemm(p, rows, relu, stream);
 }
 
 }  // namespace
@@ -255,6 +296,7 @@ SOL_API int sol_block_fwd(const sol_block_desc* desc, const void* x, const void*
         misaligned(residual))
         return SOL_ERR_ALIGN;
     hipStream_t stream = (hipStream_t)hip_stream;
+    clear_stale_error();
     if (desc->dtype == SOL_BF16) return fwd_bf16(desc, g, x, W, scale, shift, residual, y, stream);
     DirectParams p{};
     p.x = (const float*)x;
@@ -271,7 +313,7 @@ SOL_API int sol_block_fwd(const sol_block_desc* desc, const void* x, const void*
 
 SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void* x, const void* W, const void* y, void* dx,
                   float* dW, float* dscale, float* dshift, const float* scale, void* dres, const void* dx_addend,
-                  const void* dx_addend_mask, void* ws, size_t ws_bytes, void* hip_stream) {
+                  const void* dx_addend_mask, const void* dx_mask, void* ws, size_t ws_bytes, void* hip_stream) {
     Geometry g;
     if (int e = check_desc(desc, &g); e != SOL_OK) return e;
     const bool relu = (desc->flags & SOL_RELU) != 0;
@@ -280,12 +322,13 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
     if (dx_addend_mask && !dx_addend) return SOL_ERR_NULL;
     if (misaligned(dy) || misaligned(x) || misaligned(W) || misaligned(y) || misaligned(dx) || misaligned(dW) ||
         misaligned(dscale) || misaligned(dshift) || misaligned(scale) || misaligned(dres) ||
-        misaligned(dx_addend) || misaligned(dx_addend_mask) || misaligned(ws))
+        misaligned(dx_addend) || misaligned(dx_addend_mask) || misaligned(dx_mask) || misaligned(ws))
         return SOL_ERR_ALIGN;
     if (desc->dtype == SOL_BF16 && dx && desc->stride * desc->stride > kMaxClasses) return SOL_ERR_UNSUPPORTED;
     const BwdPlan plan = plan_bwd(desc, g);
     if (!ws || ws_bytes < plan.total) return SOL_ERR_WORKSPACE;
     hipStream_t stream = (hipStream_t)hip_stream;
+    clear_stale_error();
     unsigned char* wsb = (unsigned char*)ws;
     float* partial = (float*)(wsb + plan.part_off);
     float* dshift_partial = (float*)(wsb + plan.dshift_off);
@@ -301,7 +344,7 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
             PackParams pk{(const bf16_t*)W, scale, wpack, desc->C_in, desc->C_out, desc->KH, desc->KW,
                           desc->stride, desc->pad};
             if (launch_pack_dgrad_weights(pk, stream) != hipSuccess) return SOL_ERR_LAUNCH;
-            if (int e = dgrad_bf16(desc, g, dy, y, wpack, dx, dx_addend, dx_addend_mask, stream); e != SOL_OK)
+            if (int e = dgrad_bf16(desc, g, dy, y, wpack, dx, dx_addend, dx_addend_mask, dx_mask, stream); e != SOL_OK)
                 return e;
         }
         WgradParams wp{};
@@ -327,6 +370,7 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
         p.dx = (float*)dx;
         p.addend = (const float*)dx_addend;
         p.addend_mask = (const float*)dx_addend_mask;
+        p.dx_mask = (const float*)dx_mask;
         p.G = partial;
         p.dshift_partial = dshift_partial;
         p.N = desc->N; p.H = desc->H; p.W_ = desc->W; p.C_in = desc->C_in; p.C_out = desc->C_out;
@@ -352,12 +396,14 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
     return launch_wgrad_reduce(rp, stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
 }
 
-SOL_API int sol_l1_loss_grad(int32_t dtype, const void* y, const void* t, void* dy, int64_t numel, void* hip_stream) {
+SOL_API int sol_l1_loss_grad(int32_t dtype, const void* y, const void* t, void* dy, int64_t numel, int32_t mask_by_y,
+                             void* hip_stream) {
     if (dtype != SOL_F32 && dtype != SOL_BF16) return SOL_ERR_UNSUPPORTED;
     if (numel < 1) return SOL_ERR_SHAPE;
     if (!y || !t || !dy) return SOL_ERR_NULL;
     if (misaligned(y) || misaligned(t) || misaligned(dy)) return SOL_ERR_ALIGN;
-    return launch_l1_grad(dtype, y, t, dy, numel, (hipStream_t)hip_stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
+    clear_stale_error();
+    return launch_l1_grad(dtype, y, t, dy, numel, mask_by_y, (hipStream_t)hip_stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
 }
 
 SOL_API int sol_maxpool_fwd(int32_t dtype, const void* x, void* y, int32_t N, int32_t H, int32_t W, int32_t C, int32_t k,
@@ -368,6 +414,7 @@ SOL_API int sol_maxpool_fwd(int32_t dtype, const void* x, void* y, int32_t N, in
         return SOL_ERR_SHAPE;
     if (!x || !y) return SOL_ERR_NULL;
     if (misaligned(x) || misaligned(y)) return SOL_ERR_ALIGN;
+    clear_stale_error();
     return launch_maxpool(dtype, x, y, N, H, W, C, k, stride, pad, (hipStream_t)hip_stream) == hipSuccess
                ? SOL_OK : SOL_ERR_LAUNCH;
 }

@@ -50,6 +50,29 @@ __device__ __forceinline__ uintx2 mask_where_positive(uintx2 v, uintx2 m) {
     return __builtin_bit_cast(uintx2, (shortx4)(vs & keep));
 }
 
+// ---- asynchronous global -> LDS copies (16 bytes per lane, no register staging) -----------
+// The wave's 64 pieces land at lds_wave_base + 16 * lane; lds_wave_base must be wave-uniform.
+// Completion is tracked by vmcnt; nothing orders these copies against LDS reads except the
+// explicit waits and barriers below.
+__device__ __forceinline__ void dma16_to_lds(const void* gsrc, void* lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                     (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+// s_waitcnt with vmcnt = N and lgkmcnt = 0 (expcnt untouched): at most N vector-memory
+// operations of this wave still in flight, all of its LDS operations done.
+template <int N>
+__device__ __forceinline__ void wait_vm_and_lds() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (0 << 8) | ((N >> 4) << 14));
+}
+// Workgroup barrier without the memory fence of __syncthreads() (which would wait for every
+// outstanding prefetch); callers wait for exactly what they need first.
+__device__ __forceinline__ void wg_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 // ---- implicit-GEMM launch parameters -----------------------------------------------------
 // One "row class" describes which GEMM rows (pixels) a group of workgroups produces and how a
 // row and a filter tap map to a source pixel.  The forward pass has one class; the data
@@ -65,6 +88,8 @@ struct RowClass {
     int oh_mul, oh_off;     // output row   = rh * oh_mul + oh_off
     int ow_mul, ow_off;     // output col   = rw * ow_mul + ow_off
     int tile_begin;         // index of this class' first pixel tile in the launch
+    int linear;             // bit 0: source pixel index == row (1x1, stride 1, no padding);
+                            // bit 1: output pixel index == row (all rows of the output, in order)
     long long b_off;        // element offset of this class' weight matrix [Nc][Th*Tw*Cs]
 };
 
@@ -79,6 +104,7 @@ struct IgemmParams {
     const float* shift;
     const bf16_t* addend;       // residual (forward) / dx_addend (data gradient); may be null
     const bf16_t* addend_mask;  // optional gate of the addend (mask value > 0)
+    const bf16_t* out_mask;     // optional gate of the stored result (0 where mask value <= 0)
     int Hs, Ws, Cs;             // source image height, width, channels
     int Nc;                     // GEMM columns = output channels of this GEMM
     int Hout, Wout;             // output image

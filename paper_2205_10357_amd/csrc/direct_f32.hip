@@ -67,6 +67,7 @@ __global__ __launch_bounds__(256) void direct_dgrad_f32(const DirectParams p) {
         const bool keep = !p.addend_mask || p.addend_mask[idx] > 0.f;
         if (keep) acc += p.addend[idx];
     }
+    if (p.dx_mask && !(p.dx_mask[idx] > 0.f)) acc = 0.f;
     p.dx[idx] = acc;
 }
 

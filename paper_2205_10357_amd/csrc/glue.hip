@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256) void masked_copy_kernel(const T* dy, const T* 
 
 template <bool BF16>
 __global__ __launch_bounds__(256) void l1_grad_kernel(const void* yv, const void* tv, void* dyv, long long numel,
-                                                      float inv) {
+                                                      float inv, int mask_by_y) {
     const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
     if (i >= numel) return;
     float y, t;
@@ -51,7 +51,8 @@ __global__ __launch_bounds__(256) void l1_grad_kernel(const void* yv, const void
         y = reinterpret_cast<const float*>(yv)[i];
         t = reinterpret_cast<const float*>(tv)[i];
     }
-    const float d = y > t ? inv : (y < t ? -inv : 0.f);
+    float d = y > t ? inv : (y < t ? -inv : 0.f);
+    if (mask_by_y && !(y > 0.f)) d = 0.f;
     if constexpr (BF16) reinterpret_cast<bf16_t*>(dyv)[i] = f32_to_bf16(d);
     else reinterpret_cast<float*>(dyv)[i] = d;
 }
@@ -104,13 +105,14 @@ hipError_t launch_masked_copy(int dtype, const void* dy, const void* y, void* dr
     return hipGetLastError();
 }
 
-hipError_t launch_l1_grad(int dtype, const void* y, const void* t, void* dy, long long numel, hipStream_t s) {
+hipError_t launch_l1_grad(int dtype, const void* y, const void* t, void* dy, long long numel, int mask_by_y,
+                          hipStream_t s) {
     if (numel <= 0) return hipSuccess;
     const float inv = (float)(1.0 / (double)numel);
     if (dtype == 1)
-        hipLaunchKernelGGL(l1_grad_kernel<true>, dim3(blocks_for(numel)), dim3(256), 0, s, y, t, dy, numel, inv);
+        hipLaunchKernelGGL(l1_grad_kernel<true>, dim3(blocks_for(numel)), dim3(256), 0, s, y, t, dy, numel, inv, mask_by_y);
     else
-        hipLaunchKernelGGL(l1_grad_kernel<false>, dim3(blocks_for(numel)), dim3(256), 0, s, y, t, dy, numel, inv);
+        hipLaunchKernelGGL(l1_grad_kernel<false>, dim3(blocks_for(numel)), dim3(256), 0, s, y, t, dy, numel, inv, mask_by_y);
     return hipGetLastError();
 }
 

@@ -264,6 +264,8 @@ __global__ __launch_bounds__(256) void igemm_bf16_kernel(const IgemmParams p) {
                         for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
                     }
                     uintx2 o = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+                    if (p.out_mask)
+                        o = mask_where_positive(o, *reinterpret_cast<const uintx2*>(p.out_mask + obase + ch));
                     *reinterpret_cast<uintx2*>(p.out + obase + ch) = o;
                 } else {
 #pragma unroll
@@ -277,6 +279,7 @@ __global__ __launch_bounds__(256) void igemm_bf16_kernel(const IgemmParams p) {
                             if (keep) t += bf16_to_f32(a);
                         }
                         if (p.relu) t = t > 0.f ? t : 0.f;
+                        if (p.out_mask && !((short)p.out_mask[obase + ch + e] > 0)) t = 0.f;
                         p.out[obase + ch + e] = f32_to_bf16(t);
                     }
                 }

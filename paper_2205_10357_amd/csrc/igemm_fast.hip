@@ -1,0 +1,350 @@
+// Pipelined variant of the implicit-GEMM kernel for the common case: source channels a
+// multiple of 64 (every K slice of 64 lies inside one filter tap), output channels a multiple
+// of 8, no ReLU mask on the gathered operand.
+//
+//  * operands go global -> LDS with asynchronous 16-byte copies (no register staging) into a
+//    ring of NS stages; a slice is requested NS-1 iterations before it is multiplied, so HBM /
+//    L2 latency is covered by several slices of MFMA work instead of one;
+//  * padding taps and rows past the end read from a 16-byte block of zeros;
+//  * one raw workgroup barrier per slice, preceded by a vmcnt wait for exactly the slice that
+//    is about to be read (a fenced barrier would drain the whole prefetch queue);
+//  * the epilogue transposes the accumulators through LDS (fp32) so that every thread handles
+//    8 consecutive channels of one pixel: residual / addend loads and output stores are 16-byte
+//    pieces of contiguous NHWC rows, with a single rounding to bf16.
+#include <type_traits>
+
+#include "launch.h"
+
+namespace sol {
+
+__device__ __align__(16) const unsigned int kZeroChunk[4] = {0u, 0u, 0u, 0u};
+
+__device__ __forceinline__ int fast_swizzle(int row) { return (row + (row >> 3)) & 7; }
+
+__device__ __forceinline__ int fast_xcd_remap(int bid, int nblocks) {
+    const int per = nblocks >> 3, rem = nblocks & 7;
+    const int xcd = bid & 7, idx = bid >> 3;
+    const int start = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
+    return start + idx;
+}
+
+template <int BP, int BC, int WP, int WC, int NS>
+__global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
+    static_assert(WP * WC == 4, "four waves per workgroup");
+    constexpr int LP = BP / 32;            // async copies per thread and slice, pixel tile
+    constexpr int LC = BC / 32;            // async copies per thread and slice, weight tile
+    constexpr int LPS = LP + LC;
+    constexpr int TP = BP / WP / 32;
+    constexpr int TC = BC / WC / 32;
+    constexpr int STAGE = (BP + BC) * 8;   // 16-byte chunks per stage
+    constexpr int LDW = BC + 4;            // fp32 row pitch of the epilogue staging tile
+
+    HIP_DYNAMIC_SHARED(uintx4, lds)
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int bid = fast_xcd_remap(blockIdx.x, gridDim.x);
+    const int tc = bid % p.tiles_c;
+    int tp = bid / p.tiles_c;
+    int cidx = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxClasses; ++i)
+        if (i < p.ncls && tp >= p.cls[i].tile_begin) cidx = i;
+    const RowClass rc = p.cls[cidx];
+    tp -= rc.tile_begin;
+    const int row0 = tp * BP, ch0 = tc * BC;
+    const int cpt = p.Cs >> 6;                         // slices per tap
+    const int ntaps = rc.Th * rc.Tw;
+    const int nk = ntaps * cpt;
+    const long long K = (long long)ntaps * p.Cs;
+    const int img_rows = rc.Rh * rc.Rw;
+    const bf16_t* wmat = p.wmat + rc.b_off;
+    const bf16_t* zsrc = reinterpret_cast<const bf16_t*>(kZeroChunk);
+
+    // ---- epilogue role of this thread: 8 consecutive channels, rows pr0 + ps * RPP -------------
+    constexpr int CPR = BC / 8;            // 8-channel chunks per tile row
+    constexpr int RPP = 256 / CPR;         // tile rows per pass
+    constexpr int PASSES = BP / RPP;
+    const int cc = tid % CPR, pr0 = tid / CPR;
+    const int ch = ch0 + cc * 8;
+    const bool ch_ok = ch < p.Nc;
+    floatx4 sc0 = {1.f, 1.f, 1.f, 1.f}, sc1 = sc0, sh0 = {0.f, 0.f, 0.f, 0.f}, sh1 = sh0;
+    if (p.scale && ch_ok) {                // requested now, needed only after the main loop
+        sc0 = *reinterpret_cast<const floatx4*>(p.scale + ch);
+        sc1 = *reinterpret_cast<const floatx4*>(p.scale + ch + 4);
+        sh0 = *reinterpret_cast<const floatx4*>(p.shift + ch);
+        sh1 = *reinterpret_cast<const floatx4*>(p.shift + ch + 4);
+    }
+
+    // ---- what this thread copies: rows 32*i + 8*wave + (lane>>3), physical chunk lane&7 -------
+    const int j8 = lane >> 3, pc = lane & 7;
+    int rowoff[LP];                        // element offset of (row, tap 0, logical chunk)
+    unsigned hmask[LP], wmask[LP];         // taps whose source row / column lies inside the image
+#pragma unroll
+    for (int i = 0; i < LP; ++i) {
+        const int lrow = 32 * i + 8 * wave + j8;
+        const int r = row0 + lrow;
+        const int cl = pc ^ fast_swizzle(lrow);        // logical chunk stored at physical chunk pc
+        rowoff[i] = 0;
+        hmask[i] = 0u;
+        wmask[i] = 0u;
+        if (r < rc.rows) {
+            if (rc.linear & 1) {
+                rowoff[i] = r * p.Cs + cl * 8;
+                hmask[i] = 1u;
+                wmask[i] = 1u;
+            } else {
+                const int n = r / img_rows, rem = r - n * img_rows;
+                const int rh = rem / rc.Rw, rw = rem - rh * rc.Rw;
+                const int h0 = rh * rc.h_mul + rc.h_off, w0 = rw * rc.w_mul + rc.w_off;
+                rowoff[i] = ((n * p.Hs + h0) * p.Ws + w0) * p.Cs + cl * 8;
+                for (int th = 0; th < rc.Th; ++th)
+                    if ((unsigned)(h0 + th * rc.tap_step) < (unsigned)p.Hs) hmask[i] |= 1u << th;
+                for (int tw = 0; tw < rc.Tw; ++tw)
+                    if ((unsigned)(w0 + tw * rc.tap_step) < (unsigned)p.Ws) wmask[i] |= 1u << tw;
+            }
+        }
+    }
+    const bf16_t* wrow[LC];
+#pragma unroll
+    for (int i = 0; i < LC; ++i) {
+        const int lrow = 32 * i + 8 * wave + j8;
+        const int c = ch0 + lrow;
+        const int cl = pc ^ fast_swizzle(lrow);
+        wrow[i] = c < p.Nc ? wmat + (long long)c * K + cl * 8 : nullptr;
+    }
+
+    // running position of the next slice to request; a slice is requested in four parts so that
+    // the copies can be issued between the MFMAs of the slice being multiplied
+    int q_kt = 0, q_cs = 0, q_th = 0, q_tw = 0;
+    auto request_part = [&](int part) {
+        uintx4* st = lds + (q_kt % NS) * STAGE;
+        const int delta = ((q_th * p.Ws + q_tw) * rc.tap_step) * p.Cs + q_cs * 64;
+#pragma unroll
+        for (int i = 0; i < LPS; ++i) {
+            if (i < (part * LPS) / 4 || i >= ((part + 1) * LPS) / 4) continue;
+            if (i < LP) {
+                const bool ok = ((hmask[i] >> q_th) & (wmask[i] >> q_tw) & 1u) != 0u;
+                const bf16_t* src = ok ? p.src + (rowoff[i] + delta) : zsrc;
+                dma16_to_lds(src, st + (32 * i + 8 * wave) * 8);
+            } else {
+                const int iw = i - LP;
+                const bf16_t* src = wrow[iw] ? wrow[iw] + q_kt * 64 : zsrc;
+                dma16_to_lds(src, st + BP * 8 + (32 * iw + 8 * wave) * 8);
+            }
+        }
+        if (part == 3) {
+            ++q_kt;
+            if (++q_cs == cpt) {
+                q_cs = 0;
+                if (++q_tw == rc.Tw) {
+                    q_tw = 0;
+                    ++q_th;
+                }
+            }
+        }
+    };
+
+    const int wp = wave % WP, wc = wave / WP;
+    floatx16 acc[TC][TP];
+#pragma unroll
+    for (int i = 0; i < TC; ++i)
+#pragma unroll
+        for (int j = 0; j < TP; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (s < nk) {
+#pragma unroll
+            for (int part = 0; part < 4; ++part) request_part(part);
+        }
+
+    // LDS addresses of this lane's operand fragments (row and swizzle are loop invariant)
+    int wfa[TC], pfa[TP], wfx[TC], pfx[TP];
+#pragma unroll
+    for (int i = 0; i < TC; ++i) {
+        const int r = wc * (BC / WC) + i * 32 + (lane & 31);
+        wfa[i] = BP * 8 + r * 8;
+        wfx[i] = fast_swizzle(r);
+    }
+#pragma unroll
+    for (int j = 0; j < TP; ++j) {
+        const int r = wp * (BP / WP) + j * 32 + (lane & 31);
+        pfa[j] = r * 8;
+        pfx[j] = fast_swizzle(r);
+    }
+
+    // One K slice: wait for it, multiply it, and (MORE) request the slice NS-1 ahead in four
+    // parts between the MFMA groups.  The order "fragments of step ks+1, copies, MFMAs of step ks"
+    // is pinned with scheduling-group barriers: left alone, the scheduler sinks the LDS reads
+    // below the MFMAs that precede their use and every step stalls on LDS latency.
+    auto slice = [&](int kt, auto more_tag) {
+        constexpr bool MORE = decltype(more_tag)::value;
+        const uintx4* st = lds + (kt % NS) * STAGE;
+        bf16x8 wf[2][TC], pf[2][TP];
+        const int half = lane >> 5;
+#pragma unroll
+        for (int i = 0; i < TC; ++i) wf[0][i] = __builtin_bit_cast(bf16x8, st[wfa[i] + (half ^ wfx[i])]);
+#pragma unroll
+        for (int j = 0; j < TP; ++j) pf[0][j] = __builtin_bit_cast(bf16x8, st[pfa[j] + (half ^ pfx[j])]);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks < 3) {
+                const int chunk = 2 * (ks + 1) + half;
+#pragma unroll
+                for (int i = 0; i < TC; ++i) wf[nxt][i] = __builtin_bit_cast(bf16x8, st[wfa[i] + (chunk ^ wfx[i])]);
+#pragma unroll
+                for (int j = 0; j < TP; ++j) pf[nxt][j] = __builtin_bit_cast(bf16x8, st[pfa[j] + (chunk ^ pfx[j])]);
+            }
+            if constexpr (MORE) request_part(ks);
+#pragma unroll
+            for (int i = 0; i < TC; ++i)
+#pragma unroll
+                for (int j = 0; j < TP; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][i], pf[cur][j], acc[i][j], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);            // fragments of step 0
+#define SOL_SGB_STEP(KS)                                                                              \
+        if constexpr ((KS) < 3) __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);              \
+        if constexpr (MORE && (((KS) + 1) * LPS) / 4 - ((KS) * LPS) / 4 > 0)                          \
+            __builtin_amdgcn_sched_group_barrier(0x010, (((KS) + 1) * LPS) / 4 - ((KS) * LPS) / 4, 0); \
+        __builtin_amdgcn_sched_group_barrier(0x008, TC * TP, 0);
+        SOL_SGB_STEP(0)
+        SOL_SGB_STEP(1)
+        SOL_SGB_STEP(2)
+        SOL_SGB_STEP(3)
+#undef SOL_SGB_STEP
+    };
+
+    int kt = 0;
+    for (; kt + NS - 1 < nk; ++kt) {
+        // slices kt+1 .. kt+NS-2 may still be in flight; slice kt must have landed
+        wait_vm_and_lds<(NS - 2) * LPS>();
+        wg_barrier();            // every wave's part of slice kt is in LDS; slice kt-1 is no longer read
+        slice(kt, std::true_type{});
+    }
+    for (; kt < nk; ++kt) {
+        wait_vm_and_lds<0>();
+        wg_barrier();
+        slice(kt, std::false_type{});
+    }
+
+    // ---- epilogue: accumulators -> LDS [pixel][channel] fp32 -> 8 channels per thread --------
+    float* stg = reinterpret_cast<float*>(lds);
+    // output offsets of this thread's rows, and its addend pieces (requested before the barriers)
+    long long oofs[PASSES];
+    uintx4 addv[PASSES], addm[PASSES], outm[PASSES];
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) {
+        const int r = row0 + pr0 + ps * RPP;
+        oofs[ps] = -1;
+        addv[ps] = uintx4{0u, 0u, 0u, 0u};
+        addm[ps] = uintx4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+        outm[ps] = addm[ps];
+        if (r < rc.rows && ch_ok) {
+            long long opix = r;
+            if (!(rc.linear & 2)) {
+                const int n = r / img_rows, rem = r - n * img_rows;
+                const int rh = rem / rc.Rw, rw = rem - rh * rc.Rw;
+                opix = ((long long)n * p.Hout + (rh * rc.oh_mul + rc.oh_off)) * p.Wout + (rw * rc.ow_mul + rc.ow_off);
+            }
+            oofs[ps] = opix * p.Nc + ch;
+            if (p.addend) {
+                addv[ps] = *reinterpret_cast<const uintx4*>(p.addend + oofs[ps]);
+                if (p.addend_mask) addm[ps] = *reinterpret_cast<const uintx4*>(p.addend_mask + oofs[ps]);
+            }
+            if (p.out_mask) outm[ps] = *reinterpret_cast<const uintx4*>(p.out_mask + oofs[ps]);
+        }
+    }
+    wait_vm_and_lds<PASSES * 3 < 64 ? PASSES * 3 : 63>();   // LDS reads done; the epilogue loads may stay in flight
+    wg_barrier();                                   // all operand reads done, LDS can be reused
+#pragma unroll
+    for (int j = 0; j < TP; ++j) {
+        const int pr = wp * (BP / WP) + j * 32 + (lane & 31);
+#pragma unroll
+        for (int i = 0; i < TC; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int c = wc * (BC / WC) + i * 32 + 8 * q + 4 * (lane >> 5);
+                *reinterpret_cast<floatx4*>(stg + pr * LDW + c) =
+                    floatx4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+            }
+    }
+    wait_vm_and_lds<PASSES * 3 < 64 ? PASSES * 3 : 63>();
+    wg_barrier();
+
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) {
+        if (oofs[ps] < 0) continue;
+        const int pr = pr0 + ps * RPP;
+        const floatx4 a0 = *reinterpret_cast<const floatx4*>(stg + pr * LDW + cc * 8);
+        const floatx4 a1 = *reinterpret_cast<const floatx4*>(stg + pr * LDW + cc * 8 + 4);
+        float v[8] = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+        if (p.scale) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                v[e] = fmaf(sc0[e], v[e], sh0[e]);
+                v[e + 4] = fmaf(sc1[e], v[e + 4], sh1[e]);
+            }
+        }
+        if (p.addend) {
+            const uintx4 a = mask_where_positive(addv[ps], addm[ps]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                v[2 * e] += __uint_as_float(a[e] << 16);
+                v[2 * e + 1] += __uint_as_float(a[e] & 0xffff0000u);
+            }
+        }
+        if (p.relu) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+        }
+        uintx4 out = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
+                      pack_bf16x2(v[6], v[7])};
+        if (p.out_mask) out = mask_where_positive(out, outm[ps]);
+        *reinterpret_cast<uintx4*>(p.out + oofs[ps]) = out;
+    }
+}
+
+template <int BP, int BC, int WP, int WC, int NS>
+static hipError_t launch_fast_tile(const IgemmParams& p, hipStream_t stream) {
+    const size_t stages = (size_t)NS * (BP + BC) * 8 * 16;
+    const size_t epi = (size_t)BP * (BC + 4) * 4;
+    const size_t smem = stages > epi ? stages : epi;
+    auto kern = igemm_fast_kernel<BP, BC, WP, WC, NS>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(p.total_tiles), dim3(256), smem, stream, p);
+    return hipGetLastError();
+}
+
+// tile: 0 = 128 x 128, 1 = 128 pixels x 64 channels, 2 = 64 x 64, 3 = 256 x 128; stages: 2, 3 or 4
+hipError_t launch_igemm_fast(const IgemmParams& p, int tile, int stages, hipStream_t stream) {
+    if (p.total_tiles <= 0) return hipSuccess;
+    switch (tile * 8 + stages) {
+        case 0 * 8 + 2: return launch_fast_tile<128, 128, 2, 2, 2>(p, stream);
+        case 0 * 8 + 3: return launch_fast_tile<128, 128, 2, 2, 3>(p, stream);
+        case 0 * 8 + 4: return launch_fast_tile<128, 128, 2, 2, 4>(p, stream);
+        case 1 * 8 + 2: return launch_fast_tile<128, 64, 2, 2, 2>(p, stream);
+        case 1 * 8 + 3: return launch_fast_tile<128, 64, 2, 2, 3>(p, stream);
+        case 1 * 8 + 4: return launch_fast_tile<128, 64, 2, 2, 4>(p, stream);
+        case 2 * 8 + 2: return launch_fast_tile<64, 64, 2, 2, 2>(p, stream);
+        case 2 * 8 + 3: return launch_fast_tile<64, 64, 2, 2, 3>(p, stream);
+        case 2 * 8 + 4: return launch_fast_tile<64, 64, 2, 2, 4>(p, stream);
+        case 3 * 8 + 2: return launch_fast_tile<256, 128, 2, 2, 2>(p, stream);
+        case 3 * 8 + 3: return launch_fast_tile<256, 128, 2, 2, 3>(p, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+void igemm_fast_tile_shape(int tile, int* bp, int* bc) {
+    static const int shapes[4][2] = {{128, 128}, {128, 64}, {64, 64}, {256, 128}};
+    const int t = (tile < 0 || tile > 3) ? 2 : tile;
+    *bp = shapes[t][0];
+    *bc = shapes[t][1];
+}
+
+}  // namespace sol

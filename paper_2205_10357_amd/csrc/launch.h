@@ -17,6 +17,7 @@ struct DirectParams {
     float* dx;
     const float* addend;
     const float* addend_mask;
+    const float* dx_mask;
     float* G;                 // unscaled weight gradient [C_out][K] (one split)
     float* dshift_partial;    // [C_out]
     int N, H, W_, C_in, C_out, KH, KW, stride, pad, Ho, Wo, relu;
@@ -31,6 +32,8 @@ struct PackParams {            // scale-folded, per-row-class transposed weights
 
 hipError_t launch_igemm(const IgemmParams& p, int tile, bool vec, bool mask, hipStream_t stream);
 void igemm_tile_shape(int tile, int* bp, int* bc);
+hipError_t launch_igemm_fast(const IgemmParams& p, int tile, int stages, hipStream_t stream);
+void igemm_fast_tile_shape(int tile, int* bp, int* bc);
 hipError_t launch_wgrad(const WgradParams& p, bool vec, bool mask, hipStream_t stream);
 hipError_t launch_wgrad_reduce(const ReduceParams& p, hipStream_t stream);
 hipError_t launch_direct_fwd_f32(const DirectParams& p, hipStream_t s);
@@ -38,7 +41,8 @@ hipError_t launch_direct_dgrad_f32(const DirectParams& p, hipStream_t s);
 hipError_t launch_direct_wgrad_f32(const DirectParams& p, hipStream_t s);
 hipError_t launch_pack_dgrad_weights(const PackParams& p, hipStream_t s);
 hipError_t launch_masked_copy(int dtype, const void* dy, const void* y, void* dres, long long numel, hipStream_t s);
-hipError_t launch_l1_grad(int dtype, const void* y, const void* t, void* dy, long long numel, hipStream_t s);
+hipError_t launch_l1_grad(int dtype, const void* y, const void* t, void* dy, long long numel, int mask_by_y,
+                          hipStream_t s);
 hipError_t launch_maxpool(int dtype, const void* x, void* y, int N, int H, int W, int C, int k, int stride, int pad,
                           hipStream_t s);
 

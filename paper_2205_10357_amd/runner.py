@@ -7,12 +7,14 @@ section on memory consumption).  Here the schedule is the op list of a
 gradient, then one ``sol_block_bwd`` per block in reverse order.  torch is used only to
 own device buffers and the stream; every arithmetic step runs in the library's kernels.
 
-Shortcut gradients never get a pass of their own:
-  * identity shortcut: the block input's gradient is dx(conv1) + dy_tail * [y_tail > 0]; the
-    second term is added in conv1's data-gradient epilogue (``dx_addend`` = dy_tail gated by
-    ``dx_addend_mask`` = y_tail);
-  * projection shortcut: the projection has no ReLU of its own, so its backward is called
-    with the tail block's y as mask source, which makes its g equal to the tail's g.
+Layer merging across blocks in the backward pass (the paper's grouping of connected layers):
+  * every stored activation gradient is already masked by the ReLU of the block that produced
+    the activation: the loss kernel masks by its own y, and every data-gradient epilogue masks
+    by the block input it differentiates (``dx_mask``).  Blocks therefore run backward without
+    SOL_RELU and without reading their y in the two gradient GEMMs;
+  * shortcut gradients never get a pass of their own: an identity shortcut is added in the
+    epilogue of the data gradient that writes the block input's gradient (``dx_addend``), and a
+    projection shortcut simply takes the tail block's (masked) gradient as its dy.
 """
 from __future__ import annotations
 
@@ -126,47 +128,56 @@ class Sequencer:
 
     # ---------------------------------------------------------------- loss grad
     def loss_grad(self, stream=None) -> torch.Tensor:
-        last = self.ops[-1].out
-        y = self.act[last]
-        B.sol_l1_loss_grad(self.sol_dtype, y, self.target, self.dact[last], y.numel(), stream)
-        return self.dact[last]
+        last_op = self.ops[-1]
+        y = self.act[last_op.out]
+        B.sol_l1_loss_grad(self.sol_dtype, y, self.target, self.dact[last_op.out], y.numel(),
+                           bool(getattr(last_op, "relu", False)), stream)
+        return self.dact[last_op.out]
 
     # ----------------------------------------------------------------- backward
     def _plan_backward(self) -> None:
         """Resolve, once, the arguments of every backward call (reverse op order)."""
-        state: Dict[int, object] = {self.ops[-1].out: "dense"}
-        calls: List[dict] = []
-        for o in reversed(self.ops):
+        for o in self.ops:
             if o.op != "conv":
                 raise NotImplementedError("backward through the max-pool is not part of any training workload")
-            st = state.get(o.out)
-            if st is None:
-                raise RuntimeError(f"no gradient reaches {o.name}")
+        producer = {o.out: o for o in self.ops}
+        readers: Dict[int, List[ConvBlock]] = {}
+        for o in self.ops:
+            readers.setdefault(o.inp, []).append(o)
+        # where the (masked) gradient of a tensor lives: its own buffer, or the buffer of the
+        # tail block whose shortcut is the tensor's only use
+        grad_of: Dict[int, torch.Tensor] = {self.ops[-1].out: self.dact[self.ops[-1].out]}
+        shortcut: Dict[int, torch.Tensor] = {}     # shortcut gradient waiting to be added to a tensor
+        written: Dict[int, bool] = {}
+        calls: List[dict] = []
+        for o in reversed(self.ops):
+            if o.out not in grad_of:
+                if o.out in shortcut and not readers.get(o.out):
+                    if o.relu:
+                        raise NotImplementedError("shortcut-only gradient into a block with its own ReLU")
+                    grad_of[o.out] = shortcut.pop(o.out)
+                else:
+                    raise RuntimeError(f"no gradient reaches {o.name}")
             d = self.desc[o.layer]
-            if st == "dense":
-                dy, ymask, desc = self.dact[o.out], self.act[o.out], d
-            else:                                   # ("masked", tail op): gradient = dy_tail * [y_tail > 0]
-                tail: ConvBlock = st[1]
-                if o.relu:
-                    raise NotImplementedError("masked shortcut gradient into a block with its own ReLU")
-                dy, ymask = self.dact[tail.out], self.act[tail.out]
-                desc = B.BlockDesc(d.N, d.H, d.W, d.C_in, d.C_out, d.KH, d.KW, d.stride, d.pad, d.dtype,
-                                   d.flags | B.SOL_RELU)
-            call = dict(op=o, desc=desc, dy=dy, y=ymask, dx=None, addend=None, addend_mask=None)
+            desc = B.BlockDesc(d.N, d.H, d.W, d.C_in, d.C_out, d.KH, d.KW, d.stride, d.pad, d.dtype,
+                               d.flags & ~B.SOL_RELU)            # dy is stored already masked
+            call = dict(op=o, desc=desc, dy=grad_of[o.out], dx=None, addend=None, dx_mask=None)
             if o.res is not None:
-                if state.get(o.res) is not None:
-                    raise NotImplementedError("shortcut gradient arriving after another gradient")
-                state[o.res] = ("masked", o)
-            want_dx = not (o.inp == 0 and not self.wl.need_input_grad)
-            if want_dx:
-                prev = state.get(o.inp)
+                if o.res in shortcut or written.get(o.res):
+                    raise NotImplementedError("more than one shortcut into a tensor, or a late shortcut")
+                shortcut[o.res] = grad_of[o.out]
+            if not (o.inp == 0 and not self.wl.need_input_grad):
                 call["dx"] = self.dact[o.inp]
-                if prev == "dense":
-                    call["addend"] = self.dact[o.inp]
-                elif prev is not None:
-                    tail = prev[1]
-                    call["addend"], call["addend_mask"] = self.dact[tail.out], self.act[tail.out]
-                state[o.inp] = "dense"
+                if written.get(o.inp):
+                    call["addend"] = self.dact[o.inp]               # accumulate in place
+                elif o.inp in shortcut:
+                    call["addend"] = shortcut.pop(o.inp)
+                written[o.inp] = True
+                grad_of[o.inp] = self.dact[o.inp]
+                is_last_writer = readers[o.inp][0] is o
+                src = producer.get(o.inp)
+                if is_last_writer and src is not None and src.relu:
+                    call["dx_mask"] = self.act[o.inp]
             calls.append(call)
         self._bwd_calls = calls
 
@@ -174,8 +185,8 @@ class Sequencer:
         for c in self._bwd_calls:
             o = c["op"]
             p, g = self.params[o.layer], self.grads[o.layer]
-            B.sol_block_bwd(c["desc"], c["dy"], self.act[o.inp], p["W"], c["y"], c["dx"], g["dW"], g["dscale"],
-                            g["dshift"], p["scale"], None, c["addend"], c["addend_mask"], self.ws, None, stream)
+            B.sol_block_bwd(c["desc"], c["dy"], self.act[o.inp], p["W"], None, c["dx"], g["dW"], g["dscale"],
+                            g["dshift"], p["scale"], None, c["addend"], None, c["dx_mask"], self.ws, None, stream)
 
     def step(self, stream=None) -> None:
         """One pass of the whole path: forward, and for training the loss gradient and backward."""

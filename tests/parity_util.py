@@ -52,7 +52,7 @@ def make_case(seed, N, H, W, C_in, C_out, K, stride, pad, bf16=True, relu=True, 
 
 
 def gpu_block(case, need_dx=True, want_dres=False, addend=None, addend_mask=None, guard=True, accumulate=False,
-              dw_init=None):
+              dw_init=None, dx_mask=None, premasked=False):
     """Forward, L1 gradient and backward of one block on the GPU.  Returns host arrays in the
     checker's layout plus the raw device tensors."""
     d, bf16 = case["d"], case["bf16"]
@@ -87,10 +87,14 @@ def gpu_block(case, need_dx=True, want_dres=False, addend=None, addend_mask=None
     ws = torch.full((ws_bytes // 4 + 64,), float("nan"), dtype=torch.float32, device="cuda")   # poisoned
     ad = to_dev(addend, bf16) if addend is not None else None
     am = to_dev(addend_mask, bf16) if addend_mask is not None else None
+    dxm = to_dev(dx_mask, bf16) if dx_mask is not None else None
 
     B.sol_block_fwd(desc, x, w, scale, shift, res, y, None, 0)
-    B.sol_l1_loss_grad(dt, y, t, dy, y.numel())
-    B.sol_block_bwd(desc, dy, x, w, y, dx, dW, dscale, dshift, scale, dres, ad, am, ws, ws_bytes)
+    B.sol_l1_loss_grad(dt, y, t, dy, y.numel(), premasked and d.relu)
+    if premasked:           # gradient already masked by this block's ReLU: backward without flag and y
+        desc = B.BlockDesc(d.N, d.H, d.W, d.C_in, d.C_out, d.KH, d.KW, d.stride, d.pad, dt,
+                           flags & ~B.SOL_RELU)
+    B.sol_block_bwd(desc, dy, x, w, None if premasked else y, dx, dW, dscale, dshift, scale, dres, ad, am, dxm, ws, ws_bytes)
     torch.cuda.synchronize()
 
     if guard:
@@ -110,7 +114,7 @@ def gpu_block(case, need_dx=True, want_dres=False, addend=None, addend_mask=None
     return out
 
 
-def check_block(case, got, need_dx=True, addend=None, addend_mask=None, tol=None):
+def check_block(case, got, need_dx=True, addend=None, addend_mask=None, tol=None, dx_mask=None, premasked=False):
     """Element-by-element comparison with the checker; returns dict of relative L2 errors."""
     d, bf16 = case["d"], case["bf16"]
     tol = tol if tol is not None else TOL["bf16" if bf16 else "f32"]
@@ -132,6 +136,8 @@ def check_block(case, got, need_dx=True, addend=None, addend_mask=None, tol=None
         errs["mask_band"] = int(band.sum())
     # loss gradient: exact function of the stored y
     dy_o = orc.l1_grad(got["y"], case["t"])
+    if premasked and d.relu:
+        dy_o = np.where(got["y"] > 0, dy_o, 0.0)
     if bf16:
         dy_o = orc.quantize_bf16(dy_o)
     else:
@@ -142,6 +148,9 @@ def check_block(case, got, need_dx=True, addend=None, addend_mask=None, tol=None
         dx_o = g["dx"]
         if addend is not None:
             dx_o = dx_o + (np.where(addend_mask > 0, addend, 0.0) if addend_mask is not None else addend)
+        if dx_mask is not None:
+            assert np.all(got["dx"][dx_mask <= 0] == 0), "dx not exactly zero where the mask is <= 0"
+            dx_o = np.where(dx_mask > 0, dx_o, 0.0)
         errs["dx"] = rel_l2(got["dx"], dx_o)
     errs["dW"] = rel_l2(got["dW"], g["dW"])
     errs["dscale"] = rel_l2(got["dscale"], g["dscale"])

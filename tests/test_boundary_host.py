@@ -46,7 +46,7 @@ def desc(**kw):
 def test_descriptor_validation(kw, status):
     d = desc(**kw)
     assert B.sol_block_fwd(d, FAKE, FAKE, FAKE, FAKE, None, FAKE, None, 0, stream=0, check=False) == status
-    assert B.sol_block_bwd(d, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None, FAKE, 1 << 40,
+    assert B.sol_block_bwd(d, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None, None, FAKE, 1 << 40,
                            stream=0, check=False) == status
     assert B.sol_block_workspace_bytes(d, B.SOL_PASS_BWD) == 0
 
@@ -58,20 +58,20 @@ def test_pointer_validation():
     assert B.sol_block_fwd(d, FAKE + 8, FAKE, FAKE, FAKE, None, FAKE, None, 0, stream=0, check=False) == -3
     assert B.sol_block_fwd(d, FAKE, FAKE, FAKE, FAKE, FAKE + 2, FAKE, None, 0, stream=0, check=False) == -3
     args = [FAKE] * 9
-    assert B.sol_block_bwd(d, None, *args[1:], None, None, None, FAKE, 1 << 40, stream=0, check=False) == -1
+    assert B.sol_block_bwd(d, None, *args[1:], None, None, None, None, FAKE, 1 << 40, stream=0, check=False) == -1
     # ReLU block needs y for the mask; a block without ReLU does not
-    assert B.sol_block_bwd(d, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None, FAKE, 1 << 40,
+    assert B.sol_block_bwd(d, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None, None, FAKE, 1 << 40,
                            stream=0, check=False) == -1
     # addend mask without addend
-    assert B.sol_block_bwd(d, *args, None, None, FAKE, FAKE, 1 << 40, stream=0, check=False) == -1
+    assert B.sol_block_bwd(d, *args, None, None, FAKE, None, FAKE, 1 << 40, stream=0, check=False) == -1
     # workspace missing / too small
     need = B.sol_block_workspace_bytes(d, B.SOL_PASS_BWD)
     assert need > 0
-    assert B.sol_block_bwd(d, *args, None, None, None, None, 0, stream=0, check=False) == -5
-    assert B.sol_block_bwd(d, *args, None, None, None, FAKE, need - 1, stream=0, check=False) == -5
+    assert B.sol_block_bwd(d, *args, None, None, None, None, None, 0, stream=0, check=False) == -5
+    assert B.sol_block_bwd(d, *args, None, None, None, None, FAKE, need - 1, stream=0, check=False) == -5
     # bf16 data gradient supports stride <= 2
     d3 = desc(stride=3)
-    assert B.sol_block_bwd(d3, *args, None, None, None, FAKE, 1 << 40, stream=0, check=False) == -4
+    assert B.sol_block_bwd(d3, *args, None, None, None, None, FAKE, 1 << 40, stream=0, check=False) == -4
     with pytest.raises(B.SolError):
         B.sol_block_fwd(d, None, FAKE, FAKE, FAKE, None, FAKE, None, 0, stream=0)
 
@@ -88,8 +88,8 @@ def test_workspace_sizes():
 
 
 def test_glue_validation():
-    assert B.sol_l1_loss_grad(B.SOL_BF16, FAKE, FAKE, FAKE, 0, stream=0, check=False) == -2
-    assert B.sol_l1_loss_grad(5, FAKE, FAKE, FAKE, 16, stream=0, check=False) == -4
-    assert B.sol_l1_loss_grad(B.SOL_F32, None, FAKE, FAKE, 16, stream=0, check=False) == -1
+    assert B.sol_l1_loss_grad(B.SOL_BF16, FAKE, FAKE, FAKE, 0, False, stream=0, check=False) == -2
+    assert B.sol_l1_loss_grad(5, FAKE, FAKE, FAKE, 16, False, stream=0, check=False) == -4
+    assert B.sol_l1_loss_grad(B.SOL_F32, None, FAKE, FAKE, 16, False, stream=0, check=False) == -1
     assert B.sol_maxpool_fwd(B.SOL_BF16, FAKE, FAKE, 1, 8, 8, 8, 3, 2, 3, stream=0, check=False) == -2
     assert B.sol_maxpool_fwd(B.SOL_BF16, FAKE, None, 1, 8, 8, 8, 3, 2, 1, stream=0, check=False) == -1

@@ -132,6 +132,25 @@ def test_bf16_addend_mask_and_accumulate():
     np.testing.assert_allclose(acc["dshift"], base["dshift"] - 2.0, rtol=1e-6, atol=1e-7)
 
 
+@pytest.mark.parametrize("shape", [
+    dict(N=2, H=14, W=14, C_in=64, C_out=128, K=3, stride=1, pad=1, res=True),      # pipelined kernel
+    dict(N=2, H=14, W=14, C_in=128, C_out=64, K=1, stride=1, pad=0),
+    dict(N=2, H=15, W=13, C_in=64, C_out=64, K=3, stride=2, pad=1),
+    dict(N=1, H=9, W=9, C_in=24, C_out=40, K=3, stride=1, pad=1),                   # general kernel
+    dict(N=1, H=8, W=8, C_in=8, C_out=8, K=3, stride=1, pad=1, bf16=False),          # fp32 path
+])
+def test_premasked_gradient_and_dx_mask(shape):
+    """The layer-merged backward: dy arrives already masked (loss kernel with mask_by_y), the block runs
+    without SOL_RELU / y, and its dx is masked by the upstream activation in the epilogue."""
+    case = pu.make_case(21, **shape)
+    r = np.random.default_rng(22)
+    snap = wl.snap_to_bf16 if case["bf16"] else (lambda a: a)
+    dxm = snap(np.maximum(r.standard_normal(case["x"].shape), 0).astype(np.float32))
+    ad = snap(r.standard_normal(case["x"].shape).astype(np.float32))
+    got = pu.gpu_block(case, addend=ad, dx_mask=dxm, premasked=True)
+    show(f"premasked {shape}", pu.check_block(case, got, addend=ad, dx_mask=dxm, premasked=True))
+
+
 def test_runs_are_bitwise_reproducible():
     case = pu.make_case(13, 2, 28, 28, 64, 128, 3, 1, 1, res=True)
     a, b = pu.gpu_block(case), pu.gpu_block(case)
@@ -159,4 +178,4 @@ def test_error_codes_on_device_pointers():
     assert B.sol_block_fwd(d, t, t, f, f, None, None, None, 0, check=False) == -1          # y NULL
     assert B.sol_block_fwd(d, t.data_ptr() + 2, t, f, f, None, t, None, 0, check=False) == -3   # misaligned
     ws = torch.zeros(16, dtype=torch.uint8, device="cuda")
-    assert B.sol_block_bwd(d, t, t, t, t, t, f, f, f, f, None, None, None, ws, 16, check=False) == -5
+    assert B.sol_block_bwd(d, t, t, t, t, t, f, f, f, f, None, None, None, None, ws, 16, check=False) == -5
