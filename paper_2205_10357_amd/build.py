@@ -6,15 +6,15 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsol_block.so")
-SOURCES = ["api.hip", "igemm.hip", "igemm_fast.hip", "wgrad.hip", "direct_f32.hip", "glue.hip"]
-HEADERS = ["common.h", "launch.h", "classes.h", os.path.join("..", "..", "include", "sol_block.h")]
+SOURCES = ["api.hip", "igemm.hip", "igemm_fast.hip", "wgrad.hip", "wgrad_fast.hip", "direct_f32.hip", "glue.hip"]
+HEADERS = ["common.h", "launch.h", "classes.h", "sol_lds_tr.h", os.path.join("..", "..", "include", "sol_block.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
     # keep the compiler from forming packed-fp32 VALU instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-function",
+    "-Wall", "-Wno-unused-function", "-I", CSRC,
 ]
 
 

@@ -75,7 +75,10 @@ int pick_igemm_tile(const long long* class_rows, int ncls, int Nc) {
 // operand) or the general one.  SOL_IGEMM_FAST=0 forces the general kernel; SOL_FAST_TILE /
 // SOL_FAST_STAGES override the pipelined kernel's tile and ring depth (tuning experiments).
 int run_igemm(IgemmParams& p, const long long* rows, bool mask, hipStream_t stream) {
-    const bool fast_ok = !mask && (p.Cs % 64) == 0 && (p.Nc % 8) == 0 && env_int("SOL_IGEMM_FAST", 1) != 0;
+    bool few_taps = true;                       // the pipelined kernel keeps one validity bit per tap
+    for (int c = 0; c < p.ncls; ++c) few_taps = few_taps && p.cls[c].Th * p.cls[c].Tw <= 32;
+    const bool fast_ok = !mask && few_taps && (p.Cs % 64) == 0 && (p.Nc % 8) == 0 &&
+                         env_int("SOL_IGEMM_FAST", 1) != 0;
     int bp, bc, tile = 0, stages = 0;
     if (fast_ok) {
         long long slices = 0;
@@ -172,6 +175,7 @@ int fwd_bf16(const sol_block_desc* d, const Geometry& g, const void* x, const vo
     p.shift = shift;
     p.addend = (const bf16_t*)residual;
     p.addend_mask = nullptr;
+    p.src_bytes = (unsigned)(g.x_elems * 2);
     p.Hs = d->H;
     p.Ws = d->W;
     p.Cs = d->C_in;
@@ -215,6 +219,7 @@ int dgrad_bf16(const sol_block_desc* d, const Geometry& g, const void* dy, const
     p.addend = (const bf16_t*)addend;
     p.addend_mask = (const bf16_t*)addend_mask;
     p.out_mask = (const bf16_t*)dx_mask;
+    p.src_bytes = (unsigned)(g.y_elems * 2);
     p.Hs = g.Ho;
     p.Ws = g.Wo;
     p.Cs = d->C_out;
@@ -358,8 +363,17 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
         wp.Ho = g.Ho; wp.Wo = g.Wo; wp.M = (int)g.M; wp.K = (int)g.K;
         wp.splits = plan.splits; wp.m_per_split = plan.m_per_split;
         wp.tiles_k = plan.tiles_k; wp.tiles_c = plan.tiles_c;
+        wp.div_howo = make_fast_div((uint32_t)(g.Ho * g.Wo));
+        wp.div_wo = make_fast_div((uint32_t)g.Wo);
         const bool vec = (desc->C_in % 8) == 0 && (desc->C_out % 8) == 0;
-        if (launch_wgrad(wp, vec, relu, stream) != hipSuccess) return SOL_ERR_LAUNCH;
+        // pipelined kernel when dy needs no mask; SOL_WGRAD_FAST=0 forces the general kernel
+        if (vec && !relu && env_int("SOL_WGRAD_FAST", 1) != 0) {
+            int stages = env_int("SOL_WGRAD_STAGES", 2);
+            if (stages < 2 || stages > 4) stages = 3;
+            if (launch_wgrad_fast(wp, stages, stream) != hipSuccess) return SOL_ERR_LAUNCH;
+        } else if (launch_wgrad(wp, vec, relu, stream) != hipSuccess) {
+            return SOL_ERR_LAUNCH;
+        }
     } else {
         DirectParams p{};
         p.x = (const float*)x;

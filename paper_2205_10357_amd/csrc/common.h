@@ -31,8 +31,11 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
     return (bf16_t)(u >> 16);
 }
 
+// two floats -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950)
+typedef float floatx2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+    const floatx2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 // Per 16-bit lane: keep v where the bf16 value m is > 0, else +0.   (bf16 > 0  <=>  the
@@ -58,6 +61,19 @@ __device__ __forceinline__ void dma16_to_lds(const void* gsrc, void* lds_wave_ba
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
                                      (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
 }
+// Same copy through a buffer descriptor: address = base + voff + soff, where soff is wave-uniform
+// (an SGPR: no vector instruction is spent on it) and a lane whose voff is >= the descriptor's
+// size reads zeros instead of memory (the range check ignores soff).
+typedef __amdgpu_buffer_rsrc_t buffer_rsrc_t;
+__device__ __forceinline__ buffer_rsrc_t make_buffer_rsrc(const void* base, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ void dma16_buf_to_lds(buffer_rsrc_t rs, unsigned voff, unsigned soff, void* lds_wave_base) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)lds_wave_base, 16, voff,
+                                             soff, 0, 0);
+}
+constexpr unsigned kOutOfRange = 0xffffffffu;    // OR-ed into voff: lane reads zeros
+
 // s_waitcnt with vmcnt = N and lgkmcnt = 0 (expcnt untouched): at most N vector-memory
 // operations of this wave still in flight, all of its LDS operations done.
 template <int N>
@@ -105,6 +121,7 @@ struct IgemmParams {
     const bf16_t* addend;       // residual (forward) / dx_addend (data gradient); may be null
     const bf16_t* addend_mask;  // optional gate of the addend (mask value > 0)
     const bf16_t* out_mask;     // optional gate of the stored result (0 where mask value <= 0)
+    unsigned src_bytes;         // size of the gathered activation tensor
     int Hs, Ws, Cs;             // source image height, width, channels
     int Nc;                     // GEMM columns = output channels of this GEMM
     int Hout, Wout;             // output image
@@ -114,6 +131,28 @@ struct IgemmParams {
     int total_tiles;
     RowClass cls[kMaxClasses];
 };
+
+// ---- division by a launch-invariant divisor (n < 2^31): q = (mulhi(n, magic) + n) >> shift ------
+struct FastDiv {
+    uint32_t magic, shift;
+};
+inline FastDiv make_fast_div(uint32_t d) {
+    uint32_t s = 0;
+    while ((1ull << s) < d) ++s;
+    const uint64_t m = ((1ull << 32) * ((1ull << s) - d)) / d + 1;
+    return FastDiv{(uint32_t)m, s};
+}
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, FastDiv d) { return (__umulhi(n, d.magic) + n) >> d.shift; }
+
+// LDS read with transpose (16-bit elements): within each group of 16 lanes, the 16 x 8-byte
+// pieces the lanes address form a 4 x 16 matrix (4 consecutive lanes = one row of 16 elements);
+// lane i of the group receives column i, i.e. element i of each of the 4 rows.
+typedef short shortx4_lds __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uintx2 lds_read_tr_b64(const void* lds_addr) {
+    const shortx4_lds v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) shortx4_lds*)lds_addr);
+    return __builtin_bit_cast(uintx2, v);
+}
 
 // ---- weight-gradient launch parameters ---------------------------------------------------
 struct WgradParams {
@@ -128,6 +167,7 @@ struct WgradParams {
     int splits;
     int m_per_split;            // multiple of the reduction tile
     int tiles_k, tiles_c;
+    FastDiv div_howo, div_wo;   // divisors Ho*Wo and Wo
 };
 
 struct ReduceParams {

@@ -38,23 +38,40 @@ __global__ __launch_bounds__(256) void masked_copy_kernel(const T* dy, const T* 
     }
 }
 
+// dy = sign(y - t) / numel, optionally zero where y <= 0.  bf16: 8 elements (16 bytes) per thread.
 template <bool BF16>
 __global__ __launch_bounds__(256) void l1_grad_kernel(const void* yv, const void* tv, void* dyv, long long numel,
                                                       float inv, int mask_by_y) {
-    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= numel) return;
-    float y, t;
+    auto grad = [&](float y, float t) {
+        float d = y > t ? inv : (y < t ? -inv : 0.f);
+        if (mask_by_y && !(y > 0.f)) d = 0.f;
+        return d;
+    };
     if constexpr (BF16) {
-        y = bf16_to_f32(reinterpret_cast<const bf16_t*>(yv)[i]);
-        t = bf16_to_f32(reinterpret_cast<const bf16_t*>(tv)[i]);
+        const long long i8 = ((long long)blockIdx.x * 256 + threadIdx.x) * 8;
+        if (i8 >= numel) return;
+        const bf16_t* yb = reinterpret_cast<const bf16_t*>(yv);
+        const bf16_t* tb = reinterpret_cast<const bf16_t*>(tv);
+        bf16_t* db = reinterpret_cast<bf16_t*>(dyv);
+        if (i8 + 8 <= numel) {
+            const uintx4 y4 = *reinterpret_cast<const uintx4*>(yb + i8);
+            const uintx4 t4 = *reinterpret_cast<const uintx4*>(tb + i8);
+            uintx4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float lo = grad(__uint_as_float(y4[e] << 16), __uint_as_float(t4[e] << 16));
+                const float hi = grad(__uint_as_float(y4[e] & 0xffff0000u), __uint_as_float(t4[e] & 0xffff0000u));
+                o[e] = pack_bf16x2(lo, hi);
+            }
+            *reinterpret_cast<uintx4*>(db + i8) = o;
+        } else {
+            for (long long i = i8; i < numel; ++i) db[i] = f32_to_bf16(grad(bf16_to_f32(yb[i]), bf16_to_f32(tb[i])));
+        }
     } else {
-        y = reinterpret_cast<const float*>(yv)[i];
-        t = reinterpret_cast<const float*>(tv)[i];
+        const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+        if (i >= numel) return;
+        reinterpret_cast<float*>(dyv)[i] = grad(reinterpret_cast<const float*>(yv)[i], reinterpret_cast<const float*>(tv)[i]);
     }
-    float d = y > t ? inv : (y < t ? -inv : 0.f);
-    if (mask_by_y && !(y > 0.f)) d = 0.f;
-    if constexpr (BF16) reinterpret_cast<bf16_t*>(dyv)[i] = f32_to_bf16(d);
-    else reinterpret_cast<float*>(dyv)[i] = d;
 }
 
 template <bool BF16>
@@ -110,7 +127,8 @@ hipError_t launch_l1_grad(int dtype, const void* y, const void* t, void* dy, lon
     if (numel <= 0) return hipSuccess;
     const float inv = (float)(1.0 / (double)numel);
     if (dtype == 1)
-        hipLaunchKernelGGL(l1_grad_kernel<true>, dim3(blocks_for(numel)), dim3(256), 0, s, y, t, dy, numel, inv, mask_by_y);
+        hipLaunchKernelGGL(l1_grad_kernel<true>, dim3(blocks_for((numel + 7) / 8)), dim3(256), 0, s, y, t, dy, numel, inv,
+                           mask_by_y);
     else
         hipLaunchKernelGGL(l1_grad_kernel<false>, dim3(blocks_for(numel)), dim3(256), 0, s, y, t, dy, numel, inv, mask_by_y);
     return hipGetLastError();

@@ -5,7 +5,8 @@
 //  * operands go global -> LDS with asynchronous 16-byte copies (no register staging) into a
 //    ring of NS stages; a slice is requested NS-1 iterations before it is multiplied, so HBM /
 //    L2 latency is covered by several slices of MFMA work instead of one;
-//  * padding taps and rows past the end read from a 16-byte block of zeros;
+//  * the copies use buffer descriptors: the per-slice part of the address is a scalar, and padding
+//    taps / rows past the end are given an out-of-range offset, which reads zeros;
 //  * one raw workgroup barrier per slice, preceded by a vmcnt wait for exactly the slice that
 //    is about to be read (a fenced barrier would drain the whole prefetch queue);
 //  * the epilogue transposes the accumulators through LDS (fp32) so that every thread handles
@@ -16,8 +17,6 @@
 #include "launch.h"
 
 namespace sol {
-
-__device__ __align__(16) const unsigned int kZeroChunk[4] = {0u, 0u, 0u, 0u};
 
 __device__ __forceinline__ int fast_swizzle(int row) { return (row + (row >> 3)) & 7; }
 
@@ -41,7 +40,8 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
 
     HIP_DYNAMIC_SHARED(uintx4, lds)
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // wave-uniform: keeps LDS bases scalar
     const int bid = fast_xcd_remap(blockIdx.x, gridDim.x);
     const int tc = bid % p.tiles_c;
     int tp = bid / p.tiles_c;
@@ -58,7 +58,6 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
     const long long K = (long long)ntaps * p.Cs;
     const int img_rows = rc.Rh * rc.Rw;
     const bf16_t* wmat = p.wmat + rc.b_off;
-    const bf16_t* zsrc = reinterpret_cast<const bf16_t*>(kZeroChunk);
 
     // ---- epilogue role of this thread: 8 consecutive channels, rows pr0 + ps * RPP -------------
     constexpr int CPR = BC / 8;            // 8-channel chunks per tile row
@@ -76,66 +75,74 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
     }
 
     // ---- what this thread copies: rows 32*i + 8*wave + (lane>>3), physical chunk lane&7 -------
+    // Copies go through buffer descriptors: per row a loop-invariant byte offset, per slice one
+    // wave-uniform tap / channel offset; a lane whose tap falls outside the image (or whose row
+    // does not exist) gets an out-of-range offset and reads zeros.
+    const buffer_rsrc_t src_rs = make_buffer_rsrc(p.src, p.src_bytes);
+    const buffer_rsrc_t w_rs = make_buffer_rsrc(wmat, (unsigned)(K * p.Nc * 2));
     const int j8 = lane >> 3, pc = lane & 7;
-    int rowoff[LP];                        // element offset of (row, tap 0, logical chunk)
-    unsigned hmask[LP], wmask[LP];         // taps whose source row / column lies inside the image
+    unsigned rowb[LP];                     // byte offset of (row, tap 0, logical chunk), modulo 2^32
+    unsigned badtap[LP];                   // bit t set: tap t of this row lies outside the image
 #pragma unroll
     for (int i = 0; i < LP; ++i) {
         const int lrow = 32 * i + 8 * wave + j8;
         const int r = row0 + lrow;
         const int cl = pc ^ fast_swizzle(lrow);        // logical chunk stored at physical chunk pc
-        rowoff[i] = 0;
-        hmask[i] = 0u;
-        wmask[i] = 0u;
+        rowb[i] = 0u;
+        badtap[i] = 0xffffffffu;
         if (r < rc.rows) {
             if (rc.linear & 1) {
-                rowoff[i] = r * p.Cs + cl * 8;
-                hmask[i] = 1u;
-                wmask[i] = 1u;
+                rowb[i] = (unsigned)(r * p.Cs + cl * 8) * 2u;
+                badtap[i] = 0xfffffffeu;
             } else {
                 const int n = r / img_rows, rem = r - n * img_rows;
                 const int rh = rem / rc.Rw, rw = rem - rh * rc.Rw;
                 const int h0 = rh * rc.h_mul + rc.h_off, w0 = rw * rc.w_mul + rc.w_off;
-                rowoff[i] = ((n * p.Hs + h0) * p.Ws + w0) * p.Cs + cl * 8;
+                rowb[i] = (unsigned)(((n * p.Hs + h0) * p.Ws + w0) * p.Cs + cl * 8) * 2u;
+                unsigned hbad = 0u, wbad = 0u;
                 for (int th = 0; th < rc.Th; ++th)
-                    if ((unsigned)(h0 + th * rc.tap_step) < (unsigned)p.Hs) hmask[i] |= 1u << th;
+                    if ((unsigned)(h0 + th * rc.tap_step) >= (unsigned)p.Hs) hbad |= 1u << th;
                 for (int tw = 0; tw < rc.Tw; ++tw)
-                    if ((unsigned)(w0 + tw * rc.tap_step) < (unsigned)p.Ws) wmask[i] |= 1u << tw;
+                    if ((unsigned)(w0 + tw * rc.tap_step) >= (unsigned)p.Ws) wbad |= 1u << tw;
+                unsigned bad = 0u;
+                for (int th = 0; th < rc.Th; ++th)
+                    bad |= (((hbad >> th) & 1u) ? ((1u << rc.Tw) - 1u) : wbad) << (th * rc.Tw);
+                badtap[i] = bad;
             }
         }
     }
-    const bf16_t* wrow[LC];
+    unsigned wrowb[LC];
 #pragma unroll
     for (int i = 0; i < LC; ++i) {
         const int lrow = 32 * i + 8 * wave + j8;
         const int c = ch0 + lrow;
         const int cl = pc ^ fast_swizzle(lrow);
-        wrow[i] = c < p.Nc ? wmat + (long long)c * K + cl * 8 : nullptr;
+        wrowb[i] = c < p.Nc ? (unsigned)(c * (int)K + cl * 8) * 2u : kOutOfRange;
     }
 
     // running position of the next slice to request; a slice is requested in four parts so that
     // the copies can be issued between the MFMAs of the slice being multiplied
-    int q_kt = 0, q_cs = 0, q_th = 0, q_tw = 0;
+    int q_kt = 0, q_cs = 0, q_th = 0, q_tw = 0, q_tap = 0;
     auto request_part = [&](int part) {
         uintx4* st = lds + (q_kt % NS) * STAGE;
-        const int delta = ((q_th * p.Ws + q_tw) * rc.tap_step) * p.Cs + q_cs * 64;
+        const unsigned delta = (unsigned)((((q_th * p.Ws + q_tw) * rc.tap_step) * p.Cs + q_cs * 64) * 2);
 #pragma unroll
         for (int i = 0; i < LPS; ++i) {
             if (i < (part * LPS) / 4 || i >= ((part + 1) * LPS) / 4) continue;
             if (i < LP) {
-                const bool ok = ((hmask[i] >> q_th) & (wmask[i] >> q_tw) & 1u) != 0u;
-                const bf16_t* src = ok ? p.src + (rowoff[i] + delta) : zsrc;
-                dma16_to_lds(src, st + (32 * i + 8 * wave) * 8);
+                // all-ones when the tap is invalid for this row, else zero
+                const unsigned inval = (unsigned)((int)(badtap[i] << (31 - q_tap)) >> 31);
+                dma16_buf_to_lds(src_rs, (rowb[i] + delta) | inval, 0u, st + (32 * i + 8 * wave) * 8);
             } else {
                 const int iw = i - LP;
-                const bf16_t* src = wrow[iw] ? wrow[iw] + q_kt * 64 : zsrc;
-                dma16_to_lds(src, st + BP * 8 + (32 * iw + 8 * wave) * 8);
+                dma16_buf_to_lds(w_rs, wrowb[iw], (unsigned)(q_kt * 128), st + BP * 8 + (32 * iw + 8 * wave) * 8);
             }
         }
         if (part == 3) {
             ++q_kt;
             if (++q_cs == cpt) {
                 q_cs = 0;
+                ++q_tap;
                 if (++q_tw == rc.Tw) {
                     q_tw = 0;
                     ++q_th;
@@ -160,19 +167,21 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
             for (int part = 0; part < 4; ++part) request_part(part);
         }
 
-    // LDS addresses of this lane's operand fragments (row and swizzle are loop invariant)
-    int wfa[TC], pfa[TP], wfx[TC], pfx[TP];
+    // LDS chunk index (inside a stage) of this lane's operand fragment for each of the 4 steps
+    int wfo[TC][4], pfo[TP][4];
 #pragma unroll
-    for (int i = 0; i < TC; ++i) {
-        const int r = wc * (BC / WC) + i * 32 + (lane & 31);
-        wfa[i] = BP * 8 + r * 8;
-        wfx[i] = fast_swizzle(r);
-    }
+    for (int ks = 0; ks < 4; ++ks) {
+        const int chunk = 2 * ks + (lane >> 5);
 #pragma unroll
-    for (int j = 0; j < TP; ++j) {
-        const int r = wp * (BP / WP) + j * 32 + (lane & 31);
-        pfa[j] = r * 8;
-        pfx[j] = fast_swizzle(r);
+        for (int i = 0; i < TC; ++i) {
+            const int r = wc * (BC / WC) + i * 32 + (lane & 31);
+            wfo[i][ks] = BP * 8 + r * 8 + (chunk ^ fast_swizzle(r));
+        }
+#pragma unroll
+        for (int j = 0; j < TP; ++j) {
+            const int r = wp * (BP / WP) + j * 32 + (lane & 31);
+            pfo[j][ks] = r * 8 + (chunk ^ fast_swizzle(r));
+        }
     }
 
     // One K slice: wait for it, multiply it, and (MORE) request the slice NS-1 ahead in four
@@ -183,20 +192,18 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
         constexpr bool MORE = decltype(more_tag)::value;
         const uintx4* st = lds + (kt % NS) * STAGE;
         bf16x8 wf[2][TC], pf[2][TP];
-        const int half = lane >> 5;
 #pragma unroll
-        for (int i = 0; i < TC; ++i) wf[0][i] = __builtin_bit_cast(bf16x8, st[wfa[i] + (half ^ wfx[i])]);
+        for (int i = 0; i < TC; ++i) wf[0][i] = __builtin_bit_cast(bf16x8, st[wfo[i][0]]);
 #pragma unroll
-        for (int j = 0; j < TP; ++j) pf[0][j] = __builtin_bit_cast(bf16x8, st[pfa[j] + (half ^ pfx[j])]);
+        for (int j = 0; j < TP; ++j) pf[0][j] = __builtin_bit_cast(bf16x8, st[pfo[j][0]]);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             const int cur = ks & 1, nxt = cur ^ 1;
             if (ks < 3) {
-                const int chunk = 2 * (ks + 1) + half;
 #pragma unroll
-                for (int i = 0; i < TC; ++i) wf[nxt][i] = __builtin_bit_cast(bf16x8, st[wfa[i] + (chunk ^ wfx[i])]);
+                for (int i = 0; i < TC; ++i) wf[nxt][i] = __builtin_bit_cast(bf16x8, st[wfo[i][ks + 1]]);
 #pragma unroll
-                for (int j = 0; j < TP; ++j) pf[nxt][j] = __builtin_bit_cast(bf16x8, st[pfa[j] + (chunk ^ pfx[j])]);
+                for (int j = 0; j < TP; ++j) pf[nxt][j] = __builtin_bit_cast(bf16x8, st[pfo[j][ks + 1]]);
             }
             if constexpr (MORE) request_part(ks);
 #pragma unroll
@@ -235,28 +242,50 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
     float* stg = reinterpret_cast<float*>(lds);
     // output offsets of this thread's rows, and its addend pieces (requested before the barriers)
     long long oofs[PASSES];
+    bool ovalid[PASSES];
     uintx4 addv[PASSES], addm[PASSES], outm[PASSES];
+    if (rc.linear & 2) {                 // output pixel index == row: offsets advance by a constant
+        const long long o0 = (long long)(row0 + pr0) * p.Nc + ch;
+        const long long ostep = (long long)RPP * p.Nc;
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps) {
+            ovalid[ps] = ch_ok && (row0 + pr0 + ps * RPP) < rc.rows;
+            oofs[ps] = o0 + ps * ostep;
+        }
+    } else {
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps) {
+            const int r = row0 + pr0 + ps * RPP;
+            ovalid[ps] = ch_ok && r < rc.rows;
+            const int rr = ovalid[ps] ? r : 0;
+            const int n = rr / img_rows, rem = rr - n * img_rows;
+            const int rh = rem / rc.Rw, rw = rem - rh * rc.Rw;
+            const long long opix = ((long long)n * p.Hout + (rh * rc.oh_mul + rc.oh_off)) * p.Wout +
+                                   (rw * rc.ow_mul + rc.ow_off);
+            oofs[ps] = opix * p.Nc + ch;
+        }
+    }
+    const uintx4 kOnes = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
 #pragma unroll
     for (int ps = 0; ps < PASSES; ++ps) {
-        const int r = row0 + pr0 + ps * RPP;
-        oofs[ps] = -1;
         addv[ps] = uintx4{0u, 0u, 0u, 0u};
-        addm[ps] = uintx4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
-        outm[ps] = addm[ps];
-        if (r < rc.rows && ch_ok) {
-            long long opix = r;
-            if (!(rc.linear & 2)) {
-                const int n = r / img_rows, rem = r - n * img_rows;
-                const int rh = rem / rc.Rw, rw = rem - rh * rc.Rw;
-                opix = ((long long)n * p.Hout + (rh * rc.oh_mul + rc.oh_off)) * p.Wout + (rw * rc.ow_mul + rc.ow_off);
-            }
-            oofs[ps] = opix * p.Nc + ch;
-            if (p.addend) {
-                addv[ps] = *reinterpret_cast<const uintx4*>(p.addend + oofs[ps]);
-                if (p.addend_mask) addm[ps] = *reinterpret_cast<const uintx4*>(p.addend_mask + oofs[ps]);
-            }
-            if (p.out_mask) outm[ps] = *reinterpret_cast<const uintx4*>(p.out_mask + oofs[ps]);
+        addm[ps] = kOnes;
+        outm[ps] = kOnes;
+    }
+    if (p.addend) {
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps)
+            if (ovalid[ps]) addv[ps] = *reinterpret_cast<const uintx4*>(p.addend + oofs[ps]);
+        if (p.addend_mask) {
+#pragma unroll
+            for (int ps = 0; ps < PASSES; ++ps)
+                if (ovalid[ps]) addm[ps] = *reinterpret_cast<const uintx4*>(p.addend_mask + oofs[ps]);
         }
+    }
+    if (p.out_mask) {
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps)
+            if (ovalid[ps]) outm[ps] = *reinterpret_cast<const uintx4*>(p.out_mask + oofs[ps]);
     }
     wait_vm_and_lds<PASSES * 3 < 64 ? PASSES * 3 : 63>();   // LDS reads done; the epilogue loads may stay in flight
     wg_barrier();                                   // all operand reads done, LDS can be reused
@@ -275,21 +304,24 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
     wait_vm_and_lds<PASSES * 3 < 64 ? PASSES * 3 : 63>();
     wg_barrier();
 
+    // all staged rows first (independent LDS reads), then the arithmetic, then the stores
+    floatx4 va[PASSES], vb[PASSES];
 #pragma unroll
     for (int ps = 0; ps < PASSES; ++ps) {
-        if (oofs[ps] < 0) continue;
         const int pr = pr0 + ps * RPP;
-        const floatx4 a0 = *reinterpret_cast<const floatx4*>(stg + pr * LDW + cc * 8);
-        const floatx4 a1 = *reinterpret_cast<const floatx4*>(stg + pr * LDW + cc * 8 + 4);
-        float v[8] = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-        if (p.scale) {
+        va[ps] = *reinterpret_cast<const floatx4*>(stg + pr * LDW + cc * 8);
+        vb[ps] = *reinterpret_cast<const floatx4*>(stg + pr * LDW + cc * 8 + 4);
+    }
+    const bool has_addend = p.addend != nullptr, has_outmask = p.out_mask != nullptr, relu = p.relu != 0;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                v[e] = fmaf(sc0[e], v[e], sh0[e]);
-                v[e + 4] = fmaf(sc1[e], v[e + 4], sh1[e]);
-            }
+    for (int ps = 0; ps < PASSES; ++ps) {
+        float v[8] = {va[ps][0], va[ps][1], va[ps][2], va[ps][3], vb[ps][0], vb[ps][1], vb[ps][2], vb[ps][3]};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {        // identity (1, 0) when the launch has no affine
+            v[e] = fmaf(sc0[e], v[e], sh0[e]);
+            v[e + 4] = fmaf(sc1[e], v[e + 4], sh1[e]);
         }
-        if (p.addend) {
+        if (has_addend) {
             const uintx4 a = mask_where_positive(addv[ps], addm[ps]);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -297,14 +329,14 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
                 v[2 * e + 1] += __uint_as_float(a[e] & 0xffff0000u);
             }
         }
-        if (p.relu) {
+        if (relu) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+            for (int e = 0; e < 8; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;   // never -0, NaN -> 0
         }
         uintx4 out = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
                       pack_bf16x2(v[6], v[7])};
-        if (p.out_mask) out = mask_where_positive(out, outm[ps]);
-        *reinterpret_cast<uintx4*>(p.out + oofs[ps]) = out;
+        if (has_outmask) out = mask_where_positive(out, outm[ps]);
+        if (ovalid[ps]) *reinterpret_cast<uintx4*>(p.out + oofs[ps]) = out;
     }
 }
 

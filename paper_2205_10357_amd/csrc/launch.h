@@ -35,6 +35,7 @@ void igemm_tile_shape(int tile, int* bp, int* bc);
 hipError_t launch_igemm_fast(const IgemmParams& p, int tile, int stages, hipStream_t stream);
 void igemm_fast_tile_shape(int tile, int* bp, int* bc);
 hipError_t launch_wgrad(const WgradParams& p, bool vec, bool mask, hipStream_t stream);
+hipError_t launch_wgrad_fast(const WgradParams& p, int stages, hipStream_t stream);
 hipError_t launch_wgrad_reduce(const ReduceParams& p, hipStream_t stream);
 hipError_t launch_direct_fwd_f32(const DirectParams& p, hipStream_t s);
 hipError_t launch_direct_dgrad_f32(const DirectParams& p, hipStream_t s);

@@ -253,20 +253,55 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(const WgradParams p) {
 
 // One workgroup per output channel: fixed-order sum over the splits, dW = scale * G,
 // dscale = <W[co,:], G[co,:]> via wavefront shuffles, dshift = sum of the split column sums.
+// VEC: K % 4 == 0, 16-byte loads; the split loop is unrolled by 4 so that several loads are in
+// flight per thread (the order of the additions stays fixed).
+template <bool VEC>
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const ReduceParams p) {
     const int co = blockIdx.x, tid = threadIdx.x;
     const float sc = p.scale[co];
     const long long row = (long long)co * p.K;
     const long long split_stride = (long long)p.C_out * p.K;
     float dot = 0.f;
-    for (int k = tid; k < p.K; k += 256) {
-        float g = 0.f;
-        for (int s = 0; s < p.splits; ++s) g += p.partial[s * split_stride + row + k];
-        const float w = p.w_is_bf16 ? bf16_to_f32(reinterpret_cast<const bf16_t*>(p.W)[row + k])
-                                    : reinterpret_cast<const float*>(p.W)[row + k];
-        dot = fmaf(w, g, dot);
-        const float d = sc * g;
-        p.dW[row + k] = p.accumulate ? p.dW[row + k] + d : d;
+    if constexpr (VEC) {
+        for (int k = tid * 4; k < p.K; k += 1024) {
+            const float* src = p.partial + row + k;
+            floatx4 g = {0.f, 0.f, 0.f, 0.f};
+            int s = 0;
+            for (; s + 4 <= p.splits; s += 4) {
+                const floatx4 a0 = *reinterpret_cast<const floatx4*>(src + (s + 0) * split_stride);
+                const floatx4 a1 = *reinterpret_cast<const floatx4*>(src + (s + 1) * split_stride);
+                const floatx4 a2 = *reinterpret_cast<const floatx4*>(src + (s + 2) * split_stride);
+                const floatx4 a3 = *reinterpret_cast<const floatx4*>(src + (s + 3) * split_stride);
+                g = (((g + a0) + a1) + a2) + a3;
+            }
+            for (; s < p.splits; ++s) g += *reinterpret_cast<const floatx4*>(src + s * split_stride);
+            float w[4];
+            if (p.w_is_bf16) {
+                const uintx2 wb = *reinterpret_cast<const uintx2*>(reinterpret_cast<const bf16_t*>(p.W) + row + k);
+                w[0] = __uint_as_float(wb[0] << 16);
+                w[1] = __uint_as_float(wb[0] & 0xffff0000u);
+                w[2] = __uint_as_float(wb[1] << 16);
+                w[3] = __uint_as_float(wb[1] & 0xffff0000u);
+            } else {
+                const floatx4 wf = *reinterpret_cast<const floatx4*>(reinterpret_cast<const float*>(p.W) + row + k);
+                w[0] = wf[0]; w[1] = wf[1]; w[2] = wf[2]; w[3] = wf[3];
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dot = fmaf(w[e], g[e], dot);
+            floatx4 d = {sc * g[0], sc * g[1], sc * g[2], sc * g[3]};
+            if (p.accumulate) d += *reinterpret_cast<const floatx4*>(p.dW + row + k);
+            *reinterpret_cast<floatx4*>(p.dW + row + k) = d;
+        }
+    } else {
+        for (int k = tid; k < p.K; k += 256) {
+            float g = 0.f;
+            for (int s = 0; s < p.splits; ++s) g += p.partial[s * split_stride + row + k];
+            const float w = p.w_is_bf16 ? bf16_to_f32(reinterpret_cast<const bf16_t*>(p.W)[row + k])
+                                        : reinterpret_cast<const float*>(p.W)[row + k];
+            dot = fmaf(w, g, dot);
+            const float d = sc * g;
+            p.dW[row + k] = p.accumulate ? p.dW[row + k] + d : d;
+        }
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
@@ -297,7 +332,8 @@ hipError_t launch_wgrad(const WgradParams& p, bool vec, bool mask, hipStream_t s
 }
 
 hipError_t launch_wgrad_reduce(const ReduceParams& p, hipStream_t stream) {
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(p.C_out), dim3(256), 0, stream, p);
+    if ((p.K & 3) == 0) hipLaunchKernelGGL(wgrad_reduce_kernel<true>, dim3(p.C_out), dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL(wgrad_reduce_kernel<false>, dim3(p.C_out), dim3(256), 0, stream, p);
     return hipGetLastError();
 }
 
