@@ -93,6 +93,9 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, hipStream_t stre
             for (int c = 0; c < p.ncls; ++c) t128 += (rows[c] + 127) / 128;
             t128 *= (p.Nc + 127) / 128;
             tile = p.Nc <= 64 ? 1 : (t128 >= 160 ? 0 : 1);
+            // short reductions are dominated by per-workgroup latency (prologue, epilogue): many small
+            // workgroups per compute unit hide it better than few large ones
+            if (slices <= env_int("SOL_FAST_SHORTK", 4) && t128 >= 512) tile = 2;
             long long t = 0;
             igemm_fast_tile_shape(tile, &bp, &bc);
             for (int c = 0; c < p.ncls; ++c) t += (rows[c] + bp - 1) / bp;

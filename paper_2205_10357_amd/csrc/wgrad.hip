@@ -253,8 +253,8 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(const WgradParams p) {
 
 // One workgroup per output channel: fixed-order sum over the splits, dW = scale * G,
 // dscale = <W[co,:], G[co,:]> via wavefront shuffles, dshift = sum of the split column sums.
-// VEC: K % 4 == 0, 16-byte loads; the split loop is unrolled by 4 so that several loads are in
-// flight per thread (the order of the additions stays fixed).
+// VEC: K % 4 == 0, 16-byte loads; the split loop keeps 8 loads in flight per thread (the order of
+// the additions stays fixed).
 template <bool VEC>
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const ReduceParams p) {
     const int co = blockIdx.x, tid = threadIdx.x;
@@ -267,14 +267,22 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const ReduceParams p)
             const float* src = p.partial + row + k;
             floatx4 g = {0.f, 0.f, 0.f, 0.f};
             int s = 0;
-            for (; s + 4 <= p.splits; s += 4) {
-                const floatx4 a0 = *reinterpret_cast<const floatx4*>(src + (s + 0) * split_stride);
-                const floatx4 a1 = *reinterpret_cast<const floatx4*>(src + (s + 1) * split_stride);
-                const floatx4 a2 = *reinterpret_cast<const floatx4*>(src + (s + 2) * split_stride);
-                const floatx4 a3 = *reinterpret_cast<const floatx4*>(src + (s + 3) * split_stride);
-                g = (((g + a0) + a1) + a2) + a3;
+            for (; s + 8 <= p.splits; s += 8) {          // 8 independent loads in flight, fixed add order
+                floatx4 a[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) a[u] = *reinterpret_cast<const floatx4*>(src + (s + u) * split_stride);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) g += a[u];
             }
-            for (; s < p.splits; ++s) g += *reinterpret_cast<const floatx4*>(src + s * split_stride);
+            {
+                floatx4 a[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    a[u] = s + u < p.splits ? *reinterpret_cast<const floatx4*>(src + (s + u) * split_stride)
+                                            : floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int u = 0; u < 8; ++u) g += a[u];
+            }
             float w[4];
             if (p.w_is_bf16) {
                 const uintx2 wb = *reinterpret_cast<const uintx2*>(reinterpret_cast<const bf16_t*>(p.W) + row + k);
@@ -305,13 +313,20 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const ReduceParams p)
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
+    // column sums of the splits: every thread fetches its share at once (a single thread walking the
+    // splits would pay one memory latency per split), then a fixed-order sum
+    float mine = 0.f;
+    for (int s2 = tid; s2 < p.splits; s2 += 256) mine += p.dshift_partial[(long long)s2 * p.C_out + co];
     __shared__ float wsum[4];
+    __shared__ float ssum[256];
     if ((tid & 63) == 0) wsum[tid >> 6] = dot;
+    ssum[tid] = mine;
     __syncthreads();
     if (tid == 0) {
         const float ds = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
         float db = 0.f;
-        for (int s = 0; s < p.splits; ++s) db += p.dshift_partial[(long long)s * p.C_out + co];
+        const int n = p.splits < 256 ? p.splits : 256;
+        for (int s2 = 0; s2 < n; ++s2) db += ssum[s2];
         p.dscale[co] = p.accumulate ? p.dscale[co] + ds : ds;
         p.dshift[co] = p.accumulate ? p.dshift[co] + db : db;
     }
