@@ -1,0 +1,238 @@
+"""GPU parity of the five workloads, run through the layer-list sequencer (same launch configuration as
+the benchmark).  Small sizes are compared element by element; the full sizes on sampled outputs that the
+CPU checker computes one by one.  Every comparison is teacher-forced per block: the checker is fed the
+tensors the GPU stored (so the tolerance measures kernels, not bf16 drift over depth); the end-to-end
+drift of the three-block chain is reported separately.
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from oracle import oracle as orc                              # noqa: E402
+from paper_2205_10357_amd import runner, workloads as wl      # noqa: E402
+from tests import parity_util as pu                           # noqa: E402
+
+TOL = 1e-2
+
+
+def host(t, images=None):
+    """NHWC device tensor -> NCHW float64 (optionally only some images)."""
+    if images is not None:
+        t = t[torch.as_tensor(images, device=t.device)]
+    return np.ascontiguousarray(np.transpose(runner.download(t), (0, 3, 1, 2)))
+
+
+def desc_of(seq, o, n):
+    _, h, w = seq.shapes[o.inp]
+    return orc.Desc(n, h, w, o.c_in, o.c_out, o.k, o.k, o.stride, o.pad, o.relu)
+
+
+def rand_points(rng, shape, count):
+    return np.stack([rng.integers(0, s, size=count) for s in shape], axis=1).astype(np.int32)
+
+
+def rel(got, ref):
+    return pu.rel_l2(got, ref)
+
+
+def grad_source(w):
+    """tensor id -> tensor id whose stored gradient IS this tensor's gradient: a tensor that is only used
+    as a shortcut (a projection's output) takes the tail block's masked gradient as it is."""
+    src = {}
+    for o in w.conv_blocks():
+        if o.res is not None and not any(oo.inp == o.res for oo in w.conv_blocks()):
+            src[o.res] = o.out
+    return src
+
+
+# ----------------------------------------------------------------- element-by-element, small sizes
+def check_chain_elementwise(w):
+    seq = runner.Sequencer(w, "cuda:0")
+    seq.step()
+    torch.cuda.synchronize()
+    n = w.n
+    acts = {k: host(v) for k, v in seq.act.items()}
+    dacts = {k: host(v) for k, v in seq.dact.items()} if w.train else {}
+    producer = {o.out: o for o in w.ops}
+    alias = grad_source(w)
+    worst = {}
+    dx_sum = {}
+    for o in w.ops:
+        if o.op != "conv":
+            y = orc.maxpool(acts[o.inp], o.k, o.stride, o.pad)
+            assert np.array_equal(y, acts[o.out])
+            continue
+        p = w.params[o.layer]
+        d = desc_of(seq, o, n)
+        y = orc.block_fwd(d, acts[o.inp], p["W"], p["scale"], p["shift"], acts[o.res] if o.res is not None else None)
+        worst[f"{o.name}.y"] = rel(acts[o.out], y)
+        if not w.train:
+            continue
+        dy = dacts[alias.get(o.out, o.out)]
+        if o.relu:
+            assert np.all(dy[acts[o.out] <= 0] == 0), f"{o.name}: stored gradient not masked by its ReLU"
+        need_dx = o.inp in dacts
+        g = orc.block_bwd(d, dy, acts[o.inp], p["W"], acts[o.out], p["scale"], need_dx=need_dx)
+        gr = seq.grads[o.layer]
+        worst[f"{o.name}.dW"] = rel(np.transpose(runner.download(gr["dW"]), (0, 3, 1, 2)), g["dW"])
+        worst[f"{o.name}.dscale"] = rel(runner.download(gr["dscale"]), g["dscale"])
+        worst[f"{o.name}.dshift"] = rel(runner.download(gr["dshift"]), g["dshift"])
+        if need_dx:
+            dx_sum[o.inp] = dx_sum.get(o.inp, 0.0) + g["dx"]
+        if o.res is not None:
+            dx_sum[o.res] = dx_sum.get(o.res, 0.0) + dy          # shortcut: the (masked) gradient itself
+    for tid, dx in dx_sum.items():
+        if tid not in dacts or not any(oo.inp == tid for oo in w.conv_blocks()):
+            continue
+        src = producer.get(tid)
+        if src is not None and src.relu:
+            assert np.all(dacts[tid][acts[tid] <= 0] == 0)
+            dx = np.where(acts[tid] > 0, dx, 0.0)
+        worst[f"t{tid}.dx"] = rel(dacts[tid], dx)
+    if w.train:
+        last = w.ops[-1]
+        dy_o = orc.l1_grad(acts[last.out], w.target)
+        if last.relu:
+            dy_o = np.where(acts[last.out] > 0, dy_o, 0.0)
+        assert np.array_equal(dacts[last.out], orc.quantize_bf16(dy_o))
+    bad = {k: v for k, v in worst.items() if v > TOL}
+    print(f"[parity] {w.name} N={n}: worst {max(worst.values()):.3g} over {len(worst)} tensors", flush=True)
+    assert not bad, bad
+    return seq, acts
+
+
+def test_stem_block_full_size():
+    """Workload 2 at its full size (N = 32): forward, dW, dscale, dshift; no gradient to the image."""
+    w = wl.stem_bf16()
+    p = w.params[0]
+    case = dict(d=orc.Desc(w.n, 224, 224, 3, 64, 7, 7, 2, 3, True), bf16=True, x=w.x, w=p["W"], scale=p["scale"],
+                shift=p["shift"], res=None, t=w.target)
+    got = pu.gpu_block(case, need_dx=False)
+    errs = pu.check_block(case, got, need_dx=False)
+    print(f"[parity] stem N=32: {errs}", flush=True)
+
+
+def test_bottleneck_small_elementwise_and_end_to_end_drift():
+    w = wl.bottleneck14_bf16(n=4)
+    seq, acts = check_chain_elementwise(w)
+    # end-to-end: the checker's own chain, quantising where the GPU stores bf16 (informational bound)
+    a = {0: w.x.astype(np.float64)}
+    for o in w.conv_blocks():
+        p = w.params[o.layer]
+        d = desc_of(seq, o, w.n)
+        a[o.out] = orc.quantize_bf16(orc.block_fwd(d, a[o.inp], p["W"], p["scale"], p["shift"],
+                                                   a[o.res] if o.res is not None else None))
+    drift = rel(acts[w.ops[-1].out], a[w.ops[-1].out])
+    print(f"[parity] bottleneck end-to-end drift of y3 (bf16-quantised chain): {drift:.3g}", flush=True)
+    assert drift < 2e-2
+
+
+def test_stage2_small_elementwise():
+    """Workload 5 topology (stride-2 block with projection + identity blocks) at N = 2, 28x28 input."""
+    check_chain_elementwise(wl.stage2_train_bf16(n=2, faithful=True, hw=28))
+
+
+def test_resnet50_small_elementwise():
+    """Workload 4 topology (all 53 blocks + max-pool) at N = 1, 64x64 input."""
+    check_chain_elementwise(wl.resnet50_infer_bf16(n=1, hw=64))
+
+
+# ------------------------------------------------------------------------- full sizes, sampled
+def check_sampled(w, images, n_fwd=400, n_dx=300, dw_layers=(), n_dw=64, n_ch=2, seed=5):
+    rng = np.random.default_rng(seed)
+    seq = runner.Sequencer(w, "cuda:0")
+    seq.step()
+    torch.cuda.synchronize()
+    images = list(images)
+    nsub = len(images)
+    producer = {o.out: o for o in w.ops}
+    alias = grad_source(w)
+    worst = {}
+    sub_act = {}
+
+    def act(tid):
+        if tid not in sub_act:
+            sub_act[tid] = host(seq.act[tid], images)
+        return sub_act[tid]
+
+    sub_dact = {}
+
+    def dact(tid):
+        if tid not in sub_dact:
+            sub_dact[tid] = host(seq.dact[tid], images)
+        return sub_dact[tid]
+
+    dx_pts, dx_ref = {}, {}
+    for o in w.ops:
+        if o.op != "conv":
+            assert np.array_equal(orc.maxpool(act(o.inp), o.k, o.stride, o.pad), act(o.out))
+            continue
+        p = w.params[o.layer]
+        d = desc_of(seq, o, nsub)
+        res = act(o.res) if o.res is not None else None
+        pts = rand_points(rng, (nsub, o.c_out, d.Ho, d.Wo), n_fwd)
+        v, y, mag = orc.fwd_points(d, act(o.inp), p["W"], p["scale"], p["shift"], res, pts)
+        got = act(o.out)[tuple(pts.T)]
+        worst[f"{o.name}.y"] = rel(got, y)
+        if o.relu:
+            band = np.abs(v) <= 2.0 ** -19 * mag
+            assert not np.any(((got > 0) != (v > 0)) & ~band), f"{o.name}: ReLU mask mismatch"
+        if not w.train:
+            continue
+        if o.inp in seq.dact:
+            ip = dx_pts.setdefault(o.inp, rand_points(rng, (nsub,) + tuple(act(o.inp).shape[1:]), n_dx))
+            dn = orc.Desc(nsub, d.H, d.W, d.C_in, d.C_out, d.KH, d.KW, d.stride, d.pad, False)   # dy is pre-masked
+            dx_ref[o.inp] = dx_ref.get(o.inp, 0.0) + orc.dx_points(dn, dact(alias.get(o.out, o.out)), act(o.out), p["W"], p["scale"], ip)
+        if o.res is not None and o.res in seq.dact and any(oo.inp == o.res for oo in w.conv_blocks()):
+            ip = dx_pts.setdefault(o.res, rand_points(rng, (nsub,) + tuple(act(o.res).shape[1:]), n_dx))
+            dx_ref[o.res] = dx_ref.get(o.res, 0.0) + dact(o.out)[tuple(ip.T)]
+    for tid, ref in dx_ref.items():
+        ip = dx_pts[tid]
+        src = producer.get(tid)
+        got = dact(tid)[tuple(ip.T)]
+        if src is not None and src.relu:
+            keep = act(tid)[tuple(ip.T)] > 0
+            assert np.all(got[~keep] == 0)
+            ref = np.where(keep, ref, 0.0)
+        worst[f"t{tid}.dx"] = rel(got, ref)
+    sub_act.clear()
+    sub_dact.clear()
+    # weight / affine gradients need every image: a few layers, a few outputs each
+    for o in w.conv_blocks():
+        if o.name not in dw_layers:
+            continue
+        p = w.params[o.layer]
+        d = desc_of(seq, o, w.n)
+        dn = orc.Desc(w.n, d.H, d.W, d.C_in, d.C_out, d.KH, d.KW, d.stride, d.pad, False)
+        dy, y, x = host(seq.dact[alias.get(o.out, o.out)]), host(seq.act[o.out]), host(seq.act[o.inp])
+        wp = rand_points(rng, (o.c_out, o.c_in, o.k, o.k), n_dw)
+        ref = orc.dw_points(dn, dy, y, x, p["scale"], wp)
+        dW = np.transpose(runner.download(seq.grads[o.layer]["dW"]), (0, 3, 1, 2))
+        worst[f"{o.name}.dW"] = rel(dW[tuple(wp.T)], ref)
+        ch = rng.choice(o.c_out, size=n_ch, replace=False).astype(np.int32)
+        ds, db = orc.affine_grad_channels(dn, dy, y, x, p["W"], ch)
+        worst[f"{o.name}.dscale"] = rel(runner.download(seq.grads[o.layer]["dscale"])[ch], ds)
+        worst[f"{o.name}.dshift"] = rel(runner.download(seq.grads[o.layer]["dshift"])[ch], db)
+        del dy, y, x
+    bad = {k: v for k, v in worst.items() if v > TOL}
+    print(f"[parity] {w.name} N={w.n} sampled: worst {max(worst.values()):.3g} over {len(worst)} checks", flush=True)
+    assert not bad, bad
+
+
+def test_bottleneck_full_size_sampled():
+    """Workload 3 as benchmarked (N = 64)."""
+    check_sampled(wl.bottleneck14_bf16(), images=(0, 31, 63), dw_layers=("b.conv1", "b.conv2", "b.conv3"))
+
+
+def test_resnet50_full_size_sampled():
+    """Workload 4 (N = 128, 224x224, inference): every layer's output on sampled elements of two images."""
+    check_sampled(wl.resnet50_infer_bf16(), images=(0, 127), n_fwd=300)
+
+
+def test_stage2_full_size_sampled():
+    """Workload 5 (N = 128, training step over stage 2)."""
+    check_sampled(wl.stage2_train_bf16(), images=(0, 127),
+                  dw_layers=("s2.b0.conv2", "s2.b0.proj", "s2.b0.conv3", "s2.b2.conv1"), n_dw=48)
