@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--workload", type=int, default=3, choices=[2, 3, 5])
     ap.add_argument("--batch", type=int, default=0, help="override N (0 = the workload's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay a captured HIP graph of the step instead of launching from the host "
+                         "(measured: no faster here, the step is not launch-bound)")
     ap.add_argument("--cpu-sample-images", type=int, default=32)
     return ap.parse_args()
 
@@ -92,12 +95,14 @@ def main():
     seq = runner.Sequencer(wl, "cuda:0")
     stream = torch.cuda.current_stream()
 
+    # one step = the same 16 launches either way; the graph only removes per-launch host work
+    run_step = seq.capture().replay if args.graph else seq.step
     for _ in range(args.warmup):
-        seq.step()
+        run_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        seq.step()
+        run_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms = dt / args.steps * 1e3
@@ -141,6 +146,7 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": wl.name, "global_batch": n, "blocks": len(blocks),
+                   "launch": "hip_graph" if args.graph else "eager",
                    "flop_per_step": flops, "pct_mfma_peak": round(100 * value / MFMA_BF16_PEAK_TFLOPS, 2)},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,

@@ -12,7 +12,7 @@
 // The weight tile is the MFMA "A" operand and the pixel tile the "B" operand, so each lane
 // ends up with 4 consecutive channels of one pixel per accumulator quad and the epilogue
 // (affine, residual / addend, ReLU, one rounding to bf16) stores 8-byte pieces of NHWC rows.
-#include "common.h"
+#include "launch.h"
 
 namespace sol {
 
@@ -294,9 +294,9 @@ static hipError_t launch_tile(const IgemmParams& p, bool vec, bool mask, hipStre
     const size_t smem = (size_t)2 * (BP + BC) * 8 * 16;
     const dim3 grid(p.total_tiles), block(256);
     auto go = [&](auto kern) -> hipError_t {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
+        static std::atomic<size_t> granted{0};     // one per kernel instantiation (the lambda is generic)
+        if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), smem, granted); e != hipSuccess)
+            return e;
         hipLaunchKernelGGL(kern, grid, block, smem, stream, p);
         return hipGetLastError();
     };

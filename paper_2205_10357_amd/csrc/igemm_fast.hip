@@ -346,9 +346,8 @@ static hipError_t launch_fast_tile(const IgemmParams& p, hipStream_t stream) {
     const size_t epi = (size_t)BP * (BC + 4) * 4;
     const size_t smem = stages > epi ? stages : epi;
     auto kern = igemm_fast_kernel<BP, BC, WP, WC, NS>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
+    static std::atomic<size_t> granted{0};
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), smem, granted); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(p.total_tiles), dim3(256), smem, stream, p);
     return hipGetLastError();
 }

@@ -3,7 +3,19 @@
 
 #include "common.h"
 
+#include <atomic>
+
 namespace sol {
+
+// Kernels that need more than 64 KiB of dynamic LDS must have their limit raised; that is a driver
+// call, so it is made once per kernel instantiation (per process: one process drives one GPU) instead
+// of once per launch.  `granted` is the instantiation's own counter.
+inline hipError_t ensure_dynamic_lds(const void* kernel, size_t bytes, std::atomic<size_t>& granted) {
+    if (granted.load(std::memory_order_acquire) >= bytes) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) granted.store(bytes, std::memory_order_release);
+    return e;
+}
 
 struct DirectParams {
     const float* x;

@@ -12,7 +12,7 @@
 // scale[co] and derives the affine-parameter gradients:
 //   dshift[co] = sum_m g[m][co]            (column sums taken from the g blocks in registers)
 //   dscale[co] = sum_k W[co][k] * G[co][k] (equals sum_m g * conv(x,W), no z needed)
-#include "common.h"
+#include "launch.h"
 
 namespace sol {
 
@@ -336,9 +336,9 @@ hipError_t launch_wgrad(const WgradParams& p, bool vec, bool mask, hipStream_t s
     const size_t smem = (size_t)2 * WG_STAGE * 16;
     const dim3 grid(p.tiles_k * p.tiles_c * p.splits), block(256);
     auto go = [&](auto kern) -> hipError_t {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
+        static std::atomic<size_t> granted{0};     // one per kernel instantiation (the lambda is generic)
+        if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), smem, granted); e != hipSuccess)
+            return e;
         hipLaunchKernelGGL(kern, grid, block, smem, stream, p);
         return hipGetLastError();
     };

@@ -260,9 +260,8 @@ static hipError_t launch_wgf(const WgradParams& p, hipStream_t stream) {
     const size_t epi = (size_t)WGF_TILE * WGF_LDW * 4;
     const size_t smem = stages > epi ? stages : epi;
     auto kern = wgrad_fast_kernel<NS>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
+    static std::atomic<size_t> granted{0};
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), smem, granted); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(p.tiles_k * p.tiles_c * p.splits), dim3(256), smem, stream, p);
     return hipGetLastError();
 }

@@ -188,6 +188,22 @@ class Sequencer:
             B.sol_block_bwd(c["desc"], c["dy"], self.act[o.inp], p["W"], None, c["dx"], g["dW"], g["dscale"],
                             g["dshift"], p["scale"], None, c["addend"], None, c["dx_mask"], self.ws, None, stream)
 
+    def capture(self) -> "torch.cuda.CUDAGraph":
+        """Record one step (all launches, in order) into a HIP graph; ``graph.replay()`` then runs it
+        without per-launch host work.  The library itself allocates nothing and enqueues only on the
+        stream it is given, so a step is capturable as it is (no memsets are recorded)."""
+        side = torch.cuda.Stream(device=self.device)
+        side.wait_stream(torch.cuda.current_stream(self.device))
+        with torch.cuda.stream(side):
+            self.step()                      # first use of every kernel happens outside the capture
+        torch.cuda.current_stream(self.device).wait_stream(side)
+        torch.cuda.synchronize(self.device)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.step()
+        self.graph = graph
+        return graph
+
     def step(self, stream=None) -> None:
         """One pass of the whole path: forward, and for training the loss gradient and backward."""
         self.forward(stream)

@@ -236,3 +236,28 @@ def test_stage2_full_size_sampled():
     """Workload 5 (N = 128, training step over stage 2)."""
     check_sampled(wl.stage2_train_bf16(), images=(0, 127),
                   dw_layers=("s2.b0.conv2", "s2.b0.proj", "s2.b0.conv3", "s2.b2.conv1"), n_dw=48)
+
+
+def test_graph_replays_match_eager():
+    """A captured step replayed several times, with eager work and synchronisations in between, gives the
+    eager result bit for bit every time."""
+    w = wl.bottleneck14_bf16(n=8)
+    seq = runner.Sequencer(w, "cuda:0")
+    seq.step()
+    torch.cuda.synchronize()
+    ref = {k: v.clone() for k, v in seq.dact.items()}
+    ref_dw = {k: v["dW"].clone() for k, v in seq.grads.items()}
+    g = seq.capture()
+    for it in range(4):
+        for t in seq.dact.values():
+            t.fill_(7.0)                      # eager work between replays
+        for v in seq.grads.values():
+            v["dW"].zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for k in ref:
+            if any(c["dx"] is seq.dact[k] for c in seq._bwd_calls) or k == w.ops[-1].out:
+                assert torch.equal(seq.dact[k], ref[k]), (it, k)
+        for k in ref_dw:
+            assert torch.equal(seq.grads[k]["dW"], ref_dw[k]), (it, k)
