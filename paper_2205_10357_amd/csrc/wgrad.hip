@@ -253,7 +253,7 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(const WgradParams p) {
 
 // One workgroup per output channel: fixed-order sum over the splits, dW = scale * G,
 // dscale = <W[co,:], G[co,:]> via wavefront shuffles, dshift = sum of the split column sums.
-// VEC: K % 4 == 0, 16-byte loads; the split loop keeps 8 loads in flight per thread (the order of
+// VEC: K % 4 == 0, 16-byte loads; the split loop keeps up to 16 loads in flight per thread (the order of
 // the additions stays fixed).
 template <bool VEC>
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const ReduceParams p) {
@@ -267,12 +267,20 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const ReduceParams p)
             const float* src = p.partial + row + k;
             floatx4 g = {0.f, 0.f, 0.f, 0.f};
             int s = 0;
-            for (; s + 8 <= p.splits; s += 8) {          // 8 independent loads in flight, fixed add order
+            for (; s + 16 <= p.splits; s += 16) {        // 16 independent loads in flight, fixed add order
+                floatx4 a[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) a[u] = *reinterpret_cast<const floatx4*>(src + (s + u) * split_stride);
+#pragma unroll
+                for (int u = 0; u < 16; ++u) g += a[u];
+            }
+            if (s + 8 <= p.splits) {
                 floatx4 a[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) a[u] = *reinterpret_cast<const floatx4*>(src + (s + u) * split_stride);
 #pragma unroll
                 for (int u = 0; u < 8; ++u) g += a[u];
+                s += 8;
             }
             {
                 floatx4 a[8];

@@ -35,7 +35,10 @@ constexpr int WGF_OPER = WGF_BM * 16;         // 16-byte chunks of one operand t
 constexpr int WGF_STAGE = 2 * WGF_OPER;       // chunks per stage (x tile, then g tile)
 constexpr int WGF_LDW = WGF_TILE + 4;         // fp32 pitch of the output staging tile
 
-template <int NS>
+// LINEAR: 1x1, stride 1, no padding (the source pixel of row m is pixel m).  It is a template
+// parameter, and the column-sum variant of the loop is chosen once outside it, because every scalar
+// branch inside the slice loop costs a pipeline bubble that a single wave per SIMD cannot hide.
+template <int NS, bool LINEAR>
 __global__ __launch_bounds__(256) void wgrad_fast_kernel(const WgradParams p) {
     HIP_DYNAMIC_SHARED(uintx4, lds)
     constexpr int LPS = 8;                    // async copies per thread and slice (4 x rows + 4 g rows)
@@ -71,7 +74,6 @@ __global__ __launch_bounds__(256) void wgrad_fast_kernel(const WgradParams p) {
     }
     const int cg = co0 + cl * 8;              // first channel of this thread's g chunk
     const bool cg_ok = cg < p.C_out;
-    const bool linear = p.KH == 1 && p.KW == 1 && p.stride == 1 && p.pad == 0;
     const int HoWo = p.Ho * p.Wo;
     const int mrow0 = m_begin + 4 * wave + mq;            // this thread's row in slice 0, copy i adds 16*i
     unsigned xrow[4], grow[4];                             // byte offsets at slice 0 (linear x only)
@@ -92,7 +94,7 @@ __global__ __launch_bounds__(256) void wgrad_fast_kernel(const WgradParams p) {
             const int i = (part & 1) * 2 + u;
             const unsigned inval = q_sl < nvalid[i] ? 0u : kOutOfRange;
             if (part < 2) {
-                if (linear) {
+                if constexpr (LINEAR) {
                     dma16_buf_to_lds(x_rs, xrow[i] | inval, (unsigned)(q_sl * WGF_BM * p.C_in * 2),
                                      st + (16 * i + 4 * wave) * 16);
                 } else {
@@ -169,14 +171,14 @@ __global__ __launch_bounds__(256) void wgrad_fast_kernel(const WgradParams p) {
     auto frag = [](const Frags& fr, int i) {
         return __builtin_bit_cast(bf16x8, uintx4{fr.r[2 * i][0], fr.r[2 * i][1], fr.r[2 * i + 1][0], fr.r[2 * i + 1][1]});
     };
-    auto multiply = [&](Frags& fr, auto newer_tag) {     // newer_tag: reads issued after fr's that may stay in flight
+    auto multiply = [&](Frags& fr, auto newer_tag, auto shift_tag) {   // newer_tag: reads issued after fr's that may stay in flight
         lds_tr_wait<decltype(newer_tag)::value>(fr.r[0], fr.r[1], fr.r[2], fr.r[3], fr.r[4], fr.r[5], fr.r[6], fr.r[7]);
         const bf16x8 x0 = frag(fr, 0), x1 = frag(fr, 1), g0 = frag(fr, 2), g1 = frag(fr, 3);
         acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0, g0, acc[0][0], 0, 0, 0);
         acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0, g1, acc[0][1], 0, 0, 0);
         acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1, g0, acc[1][0], 0, 0, 0);
         acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1, g1, acc[1][1], 0, 0, 0);
-        if (do_shift) {
+        if constexpr (decltype(shift_tag)::value) {
             accs[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, g0, accs[0], 0, 0, 0);
             accs[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, g1, accs[1], 0, 0, 0);
         }
@@ -185,35 +187,39 @@ __global__ __launch_bounds__(256) void wgrad_fast_kernel(const WgradParams p) {
 
     // One slice.  Per step: wait for this step's fragments (requested one step earlier), request
     // the next step's, issue a quarter of the copies for the slice NS-1 ahead, multiply.
-    auto slice = [&](int sl, auto more_tag) {
+    auto slice = [&](int sl, auto more_tag, auto shift_tag) {
         constexpr bool MORE = decltype(more_tag)::value;
         const lds_addr_t xbase = lds0 + (lds_addr_t)((sl % NS) * WGF_STAGE * 16);
         Frags fa, fb;
         issue_frags(fa, xbase, std::integral_constant<int, 0>{});
         issue_frags(fb, xbase, std::integral_constant<int, 1>{});
         if constexpr (MORE) request_part(0);
-        multiply(fa, std::integral_constant<int, 8>{});
+        multiply(fa, std::integral_constant<int, 8>{}, shift_tag);
         issue_frags(fa, xbase, std::integral_constant<int, 2>{});
         if constexpr (MORE) request_part(1);
-        multiply(fb, std::integral_constant<int, 8>{});
+        multiply(fb, std::integral_constant<int, 8>{}, shift_tag);
         issue_frags(fb, xbase, std::integral_constant<int, 3>{});
         if constexpr (MORE) request_part(2);
-        multiply(fa, std::integral_constant<int, 8>{});
+        multiply(fa, std::integral_constant<int, 8>{}, shift_tag);
         if constexpr (MORE) request_part(3);
-        multiply(fb, std::integral_constant<int, 0>{});
+        multiply(fb, std::integral_constant<int, 0>{}, shift_tag);
     };
 
-    int sl = 0;
-    for (; sl + NS - 1 < nsl; ++sl) {
-        wait_vm_and_lds<(NS - 2) * LPS>();
-        wg_barrier();
-        slice(sl, std::true_type{});
-    }
-    for (; sl < nsl; ++sl) {
-        wait_vm_and_lds<0>();
-        wg_barrier();
-        slice(sl, std::false_type{});
-    }
+    auto run = [&](auto shift_tag) {
+        int sl = 0;
+        for (; sl + NS - 1 < nsl; ++sl) {
+            wait_vm_and_lds<(NS - 2) * LPS>();
+            wg_barrier();
+            slice(sl, std::true_type{}, shift_tag);
+        }
+        for (; sl < nsl; ++sl) {
+            wait_vm_and_lds<0>();
+            wg_barrier();
+            slice(sl, std::false_type{}, shift_tag);
+        }
+    };
+    if (do_shift) run(std::true_type{});
+    else run(std::false_type{});
 
     // ---- column sums: row 0 of the ones-product = accumulator element 0 of lanes 0..31 ----------
     if (do_shift && lane < 32) {
@@ -254,12 +260,12 @@ __global__ __launch_bounds__(256) void wgrad_fast_kernel(const WgradParams p) {
     }
 }
 
-template <int NS>
+template <int NS, bool LINEAR>
 static hipError_t launch_wgf(const WgradParams& p, hipStream_t stream) {
     const size_t stages = (size_t)NS * WGF_STAGE * 16;
     const size_t epi = (size_t)WGF_TILE * WGF_LDW * 4;
     const size_t smem = stages > epi ? stages : epi;
-    auto kern = wgrad_fast_kernel<NS>;
+    auto kern = wgrad_fast_kernel<NS, LINEAR>;
     static std::atomic<size_t> granted{0};
     if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), smem, granted); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(p.tiles_k * p.tiles_c * p.splits), dim3(256), smem, stream, p);
@@ -267,10 +273,11 @@ static hipError_t launch_wgf(const WgradParams& p, hipStream_t stream) {
 }
 
 hipError_t launch_wgrad_fast(const WgradParams& p, int stages, hipStream_t stream) {
+    const bool linear = p.KH == 1 && p.KW == 1 && p.stride == 1 && p.pad == 0;
     switch (stages) {
-        case 2: return launch_wgf<2>(p, stream);
-        case 3: return launch_wgf<3>(p, stream);
-        default: return launch_wgf<4>(p, stream);
+        case 2: return linear ? launch_wgf<2, true>(p, stream) : launch_wgf<2, false>(p, stream);
+        case 3: return linear ? launch_wgf<3, true>(p, stream) : launch_wgf<3, false>(p, stream);
+        default: return linear ? launch_wgf<4, true>(p, stream) : launch_wgf<4, false>(p, stream);
     }
 }
 
