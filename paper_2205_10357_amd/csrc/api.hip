@@ -3,6 +3,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "../../include/sol_block.h"
 #include "classes.h"
 #include "launch.h"
@@ -48,6 +50,41 @@ int env_int(const char* name, int fallback) {
     const char* v = getenv(name);
     if (!v || !*v) return fallback;
     return atoi(v);
+}
+
+// The weight-gradient branch of a backward call (split GEMM + reduction) does not depend on the
+// data-gradient branch (weight re-pack + GEMM), and neither fills the chip alone at ResNet sizes.
+// The call therefore forks: the weight branch is enqueued on a library-owned stream that first waits
+// for an event recorded on the caller's stream, and the caller's stream waits for the branch's end
+// event before the call's work counts as done -- seen from the caller, everything stays ordered on
+// the caller's stream.  One lane (stream + two events, default priority) per device, created on the
+// first backward call on that device and kept until the process ends; the mutex makes the
+// record/wait pairs of concurrent host threads atomic.  The fork is off unless SOL_BWD_OVERLAP=1: launched from the host the event traffic costs more than the
+// overlap gains (measured); inside a captured graph it gains a few percent.
+struct SideLane {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    int state = 0;                      // 0 untried, 1 ready, -1 creation failed (fork stays off)
+};
+constexpr int kMaxDevices = 64;
+SideLane g_lanes[kMaxDevices];
+std::mutex g_lane_mutex;
+
+// Caller holds g_lane_mutex.
+SideLane* side_lane() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    SideLane& l = g_lanes[dev];
+    if (l.state == 0) {
+        l.state = -1;
+        if (hipStreamCreateWithFlags(&l.stream, hipStreamNonBlocking) == hipSuccess &&
+            hipEventCreateWithFlags(&l.fork, hipEventDisableTiming) == hipSuccess &&
+            hipEventCreateWithFlags(&l.join, hipEventDisableTiming) == hipSuccess)
+            l.state = 1;
+        else
+            (void)hipGetLastError();
+    }
+    return l.state == 1 ? &l : nullptr;
 }
 
 // Largest tile that still yields about one workgroup per compute unit; small problems fall
@@ -342,42 +379,7 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
     float* dshift_partial = (float*)(wsb + plan.dshift_off);
     const void* ymask = relu ? y : nullptr;
 
-    if (dres) {
-        if (launch_masked_copy(desc->dtype, dy, ymask, dres, g.y_elems, stream) != hipSuccess) return SOL_ERR_LAUNCH;
-    }
-
-    if (desc->dtype == SOL_BF16) {
-        if (dx) {
-            bf16_t* wpack = (bf16_t*)(wsb + plan.wpack_off);
-            PackParams pk{(const bf16_t*)W, scale, wpack, desc->C_in, desc->C_out, desc->KH, desc->KW,
-                          desc->stride, desc->pad};
-            if (launch_pack_dgrad_weights(pk, stream) != hipSuccess) return SOL_ERR_LAUNCH;
-            if (int e = dgrad_bf16(desc, g, dy, y, wpack, dx, dx_addend, dx_addend_mask, dx_mask, stream); e != SOL_OK)
-                return e;
-        }
-        WgradParams wp{};
-        wp.dy = (const bf16_t*)dy;
-        wp.y = (const bf16_t*)ymask;
-        wp.x = (const bf16_t*)x;
-        wp.partial = partial;
-        wp.dshift_partial = dshift_partial;
-        wp.N = desc->N; wp.H = desc->H; wp.W = desc->W; wp.C_in = desc->C_in; wp.C_out = desc->C_out;
-        wp.KH = desc->KH; wp.KW = desc->KW; wp.stride = desc->stride; wp.pad = desc->pad;
-        wp.Ho = g.Ho; wp.Wo = g.Wo; wp.M = (int)g.M; wp.K = (int)g.K;
-        wp.splits = plan.splits; wp.m_per_split = plan.m_per_split;
-        wp.tiles_k = plan.tiles_k; wp.tiles_c = plan.tiles_c;
-        wp.div_howo = make_fast_div((uint32_t)(g.Ho * g.Wo));
-        wp.div_wo = make_fast_div((uint32_t)g.Wo);
-        const bool vec = (desc->C_in % 8) == 0 && (desc->C_out % 8) == 0;
-        // pipelined kernel when dy needs no mask; SOL_WGRAD_FAST=0 forces the general kernel
-        if (vec && !relu && env_int("SOL_WGRAD_FAST", 1) != 0) {
-            int stages = env_int("SOL_WGRAD_STAGES", 2);
-            if (stages < 2 || stages > 4) stages = 3;
-            if (launch_wgrad_fast(wp, stages, stream) != hipSuccess) return SOL_ERR_LAUNCH;
-        } else if (launch_wgrad(wp, vec, relu, stream) != hipSuccess) {
-            return SOL_ERR_LAUNCH;
-        }
-    } else {
+    auto direct_params = [&]() {
         DirectParams p{};
         p.x = (const float*)x;
         p.W = (const float*)W;
@@ -393,24 +395,87 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
         p.N = desc->N; p.H = desc->H; p.W_ = desc->W; p.C_in = desc->C_in; p.C_out = desc->C_out;
         p.KH = desc->KH; p.KW = desc->KW; p.stride = desc->stride; p.pad = desc->pad;
         p.Ho = g.Ho; p.Wo = g.Wo; p.relu = relu ? 1 : 0;
-        if (dx && launch_direct_dgrad_f32(p, stream) != hipSuccess) return SOL_ERR_LAUNCH;
-        if (launch_direct_wgrad_f32(p, stream) != hipSuccess) return SOL_ERR_LAUNCH;
-    }
+        return p;
+    };
 
-    ReduceParams rp{};
-    rp.partial = partial;
-    rp.dshift_partial = dshift_partial;
-    rp.W = W;
-    rp.scale = scale;
-    rp.dW = dW;
-    rp.dscale = dscale;
-    rp.dshift = dshift;
-    rp.C_out = desc->C_out;
-    rp.K = (int)g.K;
-    rp.splits = plan.splits;
-    rp.accumulate = (desc->flags & SOL_DW_ACCUMULATE) ? 1 : 0;
-    rp.w_is_bf16 = desc->dtype == SOL_BF16 ? 1 : 0;
-    return launch_wgrad_reduce(rp, stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
+    // ---- data branch: shortcut gradient, weight re-pack, data-gradient GEMM (caller's stream) ----
+    auto data_branch = [&](hipStream_t st) -> int {
+        if (dres && launch_masked_copy(desc->dtype, dy, ymask, dres, g.y_elems, st) != hipSuccess)
+            return SOL_ERR_LAUNCH;
+        if (!dx) return SOL_OK;
+        if (desc->dtype == SOL_BF16) {
+            bf16_t* wpack = (bf16_t*)(wsb + plan.wpack_off);
+            PackParams pk{(const bf16_t*)W, scale, wpack, desc->C_in, desc->C_out, desc->KH, desc->KW,
+                          desc->stride, desc->pad};
+            if (launch_pack_dgrad_weights(pk, st) != hipSuccess) return SOL_ERR_LAUNCH;
+            return dgrad_bf16(desc, g, dy, y, wpack, dx, dx_addend, dx_addend_mask, dx_mask, st);
+        }
+        DirectParams p = direct_params();
+        return launch_direct_dgrad_f32(p, st) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
+    };
+
+    // ---- weight branch: split weight-gradient GEMM, then the reduction that also finishes dscale, dshift ----
+    auto weight_branch = [&](hipStream_t st) -> int {
+        if (desc->dtype == SOL_BF16) {
+            WgradParams wp{};
+            wp.dy = (const bf16_t*)dy;
+            wp.y = (const bf16_t*)ymask;
+            wp.x = (const bf16_t*)x;
+            wp.partial = partial;
+            wp.dshift_partial = dshift_partial;
+            wp.N = desc->N; wp.H = desc->H; wp.W = desc->W; wp.C_in = desc->C_in; wp.C_out = desc->C_out;
+            wp.KH = desc->KH; wp.KW = desc->KW; wp.stride = desc->stride; wp.pad = desc->pad;
+            wp.Ho = g.Ho; wp.Wo = g.Wo; wp.M = (int)g.M; wp.K = (int)g.K;
+            wp.splits = plan.splits; wp.m_per_split = plan.m_per_split;
+            wp.tiles_k = plan.tiles_k; wp.tiles_c = plan.tiles_c;
+            wp.div_howo = make_fast_div((uint32_t)(g.Ho * g.Wo));
+            wp.div_wo = make_fast_div((uint32_t)g.Wo);
+            const bool vec = (desc->C_in % 8) == 0 && (desc->C_out % 8) == 0;
+            // pipelined kernel when dy needs no mask; SOL_WGRAD_FAST=0 forces the general kernel
+            if (vec && !relu && env_int("SOL_WGRAD_FAST", 1) != 0) {
+                int stages = env_int("SOL_WGRAD_STAGES", 2);
+                if (stages < 2 || stages > 4) stages = 3;
+                if (launch_wgrad_fast(wp, stages, st) != hipSuccess) return SOL_ERR_LAUNCH;
+            } else if (launch_wgrad(wp, vec, relu, st) != hipSuccess) {
+                return SOL_ERR_LAUNCH;
+            }
+        } else {
+            DirectParams p = direct_params();
+            if (launch_direct_wgrad_f32(p, st) != hipSuccess) return SOL_ERR_LAUNCH;
+        }
+        ReduceParams rp{};
+        rp.partial = partial;
+        rp.dshift_partial = dshift_partial;
+        rp.W = W;
+        rp.scale = scale;
+        rp.dW = dW;
+        rp.dscale = dscale;
+        rp.dshift = dshift;
+        rp.C_out = desc->C_out;
+        rp.K = (int)g.K;
+        rp.splits = plan.splits;
+        rp.accumulate = (desc->flags & SOL_DW_ACCUMULATE) ? 1 : 0;
+        rp.w_is_bf16 = desc->dtype == SOL_BF16 ? 1 : 0;
+        return launch_wgrad_reduce(rp, st) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
+    };
+
+    if ((dx || dres) && env_int("SOL_BWD_OVERLAP", 0) != 0) {
+        std::lock_guard<std::mutex> hold(g_lane_mutex);
+        if (SideLane* lane = side_lane()) {
+            if (hipEventRecord(lane->fork, stream) != hipSuccess ||
+                hipStreamWaitEvent(lane->stream, lane->fork, 0) != hipSuccess)
+                return SOL_ERR_LAUNCH;
+            const int ew = weight_branch(lane->stream);
+            // the join is enqueued whatever happened, so the lane never holds work the caller's stream
+            // does not wait for
+            const bool joined = hipEventRecord(lane->join, lane->stream) == hipSuccess;
+            const int ed = data_branch(stream);
+            if (!joined || hipStreamWaitEvent(stream, lane->join, 0) != hipSuccess) return SOL_ERR_LAUNCH;
+            return ew != SOL_OK ? ew : ed;
+        }
+    }
+    if (int e = data_branch(stream); e != SOL_OK) return e;
+    return weight_branch(stream);
 }
 
 SOL_API int sol_l1_loss_grad(int32_t dtype, const void* y, const void* t, void* dy, int64_t numel, int32_t mask_by_y,

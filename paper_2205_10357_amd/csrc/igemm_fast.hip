@@ -123,12 +123,12 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
     // running position of the next slice to request; a slice is requested in four parts so that
     // the copies can be issued between the MFMAs of the slice being multiplied
     int q_kt = 0, q_cs = 0, q_th = 0, q_tw = 0, q_tap = 0;
-    auto request_part = [&](int part) {
+    auto request_part = [&](int part, int nparts) {
         uintx4* st = lds + (q_kt % NS) * STAGE;
         const unsigned delta = (unsigned)((((q_th * p.Ws + q_tw) * rc.tap_step) * p.Cs + q_cs * 64) * 2);
 #pragma unroll
         for (int i = 0; i < LPS; ++i) {
-            if (i < (part * LPS) / 4 || i >= ((part + 1) * LPS) / 4) continue;
+            if (i < (part * LPS) / nparts || i >= ((part + 1) * LPS) / nparts) continue;
             if (i < LP) {
                 // all-ones when the tap is invalid for this row, else zero
                 const unsigned inval = (unsigned)((int)(badtap[i] << (31 - q_tap)) >> 31);
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
                 dma16_buf_to_lds(w_rs, wrowb[iw], (unsigned)(q_kt * 128), st + BP * 8 + (32 * iw + 8 * wave) * 8);
             }
         }
-        if (part == 3) {
+        if (part == nparts - 1) {
             ++q_kt;
             if (++q_cs == cpt) {
                 q_cs = 0;
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
     for (int s = 0; s < NS - 1; ++s)
         if (s < nk) {
 #pragma unroll
-            for (int part = 0; part < 4; ++part) request_part(part);
+            for (int part = 0; part < 4; ++part) request_part(part, 4);
         }
 
     // LDS chunk index (inside a stage) of this lane's operand fragment for each of the 4 steps
@@ -184,58 +184,114 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
         }
     }
 
-    // One K slice: wait for it, multiply it, and (MORE) request the slice NS-1 ahead in four
-    // parts between the MFMA groups.  The order "fragments of step ks+1, copies, MFMAs of step ks"
-    // is pinned with scheduling-group barriers: left alone, the scheduler sinks the LDS reads
-    // below the MFMAs that precede their use and every step stalls on LDS latency.
-    auto slice = [&](int kt, auto more_tag) {
-        constexpr bool MORE = decltype(more_tag)::value;
-        const uintx4* st = lds + (kt % NS) * STAGE;
-        bf16x8 wf[2][TC], pf[2][TP];
+    bf16x8 wf[2][TC], pf[2][TP];           // operand fragments of two consecutive steps
+    auto read_frags = [&](int buf, const uintx4* st, int ks) {
 #pragma unroll
-        for (int i = 0; i < TC; ++i) wf[0][i] = __builtin_bit_cast(bf16x8, st[wfo[i][0]]);
+        for (int i = 0; i < TC; ++i) wf[buf][i] = __builtin_bit_cast(bf16x8, st[wfo[i][ks]]);
 #pragma unroll
-        for (int j = 0; j < TP; ++j) pf[0][j] = __builtin_bit_cast(bf16x8, st[pfo[j][0]]);
+        for (int j = 0; j < TP; ++j) pf[buf][j] = __builtin_bit_cast(bf16x8, st[pfo[j][ks]]);
+    };
+    auto multiply = [&](int buf) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const int cur = ks & 1, nxt = cur ^ 1;
-            if (ks < 3) {
+        for (int i = 0; i < TC; ++i)
 #pragma unroll
-                for (int i = 0; i < TC; ++i) wf[nxt][i] = __builtin_bit_cast(bf16x8, st[wfo[i][ks + 1]]);
-#pragma unroll
-                for (int j = 0; j < TP; ++j) pf[nxt][j] = __builtin_bit_cast(bf16x8, st[pfo[j][ks + 1]]);
-            }
-            if constexpr (MORE) request_part(ks);
-#pragma unroll
-            for (int i = 0; i < TC; ++i)
-#pragma unroll
-                for (int j = 0; j < TP; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][i], pf[cur][j], acc[i][j], 0, 0, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);            // fragments of step 0
-#define SOL_SGB_STEP(KS)                                                                              \
-        if constexpr ((KS) < 3) __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);              \
-        if constexpr (MORE && (((KS) + 1) * LPS) / 4 - ((KS) * LPS) / 4 > 0)                          \
-            __builtin_amdgcn_sched_group_barrier(0x010, (((KS) + 1) * LPS) / 4 - ((KS) * LPS) / 4, 0); \
-        __builtin_amdgcn_sched_group_barrier(0x008, TC * TP, 0);
-        SOL_SGB_STEP(0)
-        SOL_SGB_STEP(1)
-        SOL_SGB_STEP(2)
-        SOL_SGB_STEP(3)
-#undef SOL_SGB_STEP
+            for (int j = 0; j < TP; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][i], pf[buf][j], acc[i][j], 0, 0, 0);
     };
 
-    int kt = 0;
-    for (; kt + NS - 1 < nk; ++kt) {
-        // slices kt+1 .. kt+NS-2 may still be in flight; slice kt must have landed
-        wait_vm_and_lds<(NS - 2) * LPS>();
-        wg_barrier();            // every wave's part of slice kt is in LDS; slice kt-1 is no longer read
-        slice(kt, std::true_type{});
-    }
-    for (; kt < nk; ++kt) {
-        wait_vm_and_lds<0>();
+    if constexpr (NS >= 3) {
+        // Slices overlap: the fragments of a slice's first step are read during the last step of the
+        // slice before it, so the matrix pipe never waits for LDS latency at a slice boundary.  The one
+        // barrier per slice sits in the middle of slice kt (after its step 0 is issued) and does two jobs:
+        // slice kt+1 has landed for every wave (each waited for its own copies first), and no wave reads
+        // slice kt-1 any more, so its stage may be overwritten by the copies of slice kt+NS-1, which are
+        // issued after the barrier in three parts between the MFMA groups.  The instruction order
+        // "fragments of the next step, copies, MFMAs of this step" is pinned with scheduling-group
+        // barriers: left alone, the scheduler sinks the LDS reads below the MFMAs that precede their use.
+        auto slice = [&](int kt, auto next_tag, auto more_tag) {
+            constexpr bool NEXT = decltype(next_tag)::value;   // slice kt+1 exists
+            constexpr bool MORE = decltype(more_tag)::value;   // slice kt+NS-1 exists and is requested here
+            const uintx4* st = lds + (kt % NS) * STAGE;
+            const uintx4* stn = lds + ((kt + 1) % NS) * STAGE;
+            read_frags(1, st, 1);
+            multiply(0);
+            __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, TC * TP, 0);
+            read_frags(0, st, 2);
+            __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);
+            if constexpr (NEXT) {
+                // copies of slices kt+2 .. kt+NS-2 may stay in flight (none once requests have stopped)
+                __builtin_amdgcn_s_waitcnt(MORE ? (0x0f70 | (((NS - 3) * LPS) & 15) | ((((NS - 3) * LPS) >> 4) << 14))
+                                                : 0x0f70);
+                wg_barrier();
+            }
+            if constexpr (MORE) request_part(0, 3);
+            multiply(1);
+            if constexpr (MORE && (LPS / 3) > 0) __builtin_amdgcn_sched_group_barrier(0x010, LPS / 3, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, TC * TP, 0);
+            read_frags(1, st, 3);
+            if constexpr (MORE) request_part(1, 3);
+            multiply(0);
+            __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);
+            if constexpr (MORE && (2 * LPS) / 3 - LPS / 3 > 0)
+                __builtin_amdgcn_sched_group_barrier(0x010, (2 * LPS) / 3 - LPS / 3, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, TC * TP, 0);
+            if constexpr (NEXT) read_frags(0, stn, 0);
+            if constexpr (MORE) request_part(2, 3);
+            multiply(1);
+            if constexpr (NEXT) __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);
+            if constexpr (MORE && LPS - (2 * LPS) / 3 > 0)
+                __builtin_amdgcn_sched_group_barrier(0x010, LPS - (2 * LPS) / 3, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, TC * TP, 0);
+        };
+
+        // slice 0 must have landed; slices 1 .. NS-2 may still be in flight if that many exist
+        if (nk >= NS - 1) wait_vm_and_lds<(NS - 2) * LPS>();
+        else wait_vm_and_lds<0>();
         wg_barrier();
-        slice(kt, std::false_type{});
+        read_frags(0, lds, 0);
+        int kt = 0;
+        for (; kt + NS - 1 < nk; ++kt) slice(kt, std::true_type{}, std::true_type{});
+        for (; kt + 1 < nk; ++kt) slice(kt, std::true_type{}, std::false_type{});
+        slice(kt, std::false_type{}, std::false_type{});
+    } else {
+        // Two stages: one K slice = wait for it, multiply it, and (MORE) request the next one in four
+        // parts between the MFMA groups; one barrier at the start of every slice.
+        auto slice = [&](int kt, auto more_tag) {
+            constexpr bool MORE = decltype(more_tag)::value;
+            const uintx4* st = lds + (kt % NS) * STAGE;
+            read_frags(0, st, 0);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const int cur = ks & 1, nxt = cur ^ 1;
+                if (ks < 3) read_frags(nxt, st, ks + 1);
+                if constexpr (MORE) request_part(ks, 4);
+                multiply(cur);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);            // fragments of step 0
+#define SOL_SGB_STEP(KS)                                                                              \
+            if constexpr ((KS) < 3) __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);              \
+            if constexpr (MORE && (((KS) + 1) * LPS) / 4 - ((KS) * LPS) / 4 > 0)                          \
+                __builtin_amdgcn_sched_group_barrier(0x010, (((KS) + 1) * LPS) / 4 - ((KS) * LPS) / 4, 0); \
+            __builtin_amdgcn_sched_group_barrier(0x008, TC * TP, 0);
+            SOL_SGB_STEP(0)
+            SOL_SGB_STEP(1)
+            SOL_SGB_STEP(2)
+            SOL_SGB_STEP(3)
+#undef SOL_SGB_STEP
+        };
+
+        int kt = 0;
+        for (; kt + NS - 1 < nk; ++kt) {
+            wait_vm_and_lds<(NS - 2) * LPS>();   // slice kt must have landed
+            wg_barrier();            // every wave's part of slice kt is in LDS; slice kt-1 is no longer read
+            slice(kt, std::true_type{});
+        }
+        for (; kt < nk; ++kt) {
+            wait_vm_and_lds<0>();
+            wg_barrier();
+            slice(kt, std::false_type{});
+        }
     }
 
     // ---- epilogue: accumulators -> LDS [pixel][channel] fp32 -> 8 channels per thread --------
