@@ -34,9 +34,12 @@ def parse():
     ap.add_argument("--workload", type=int, default=3, choices=[2, 3, 5])
     ap.add_argument("--batch", type=int, default=0, help="override N (0 = the workload's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--graph", action="store_true",
-                    help="replay a captured HIP graph of the step instead of launching from the host "
-                         "(measured: no faster here, the step is not launch-bound)")
+    ap.add_argument("--launch", choices=["eager", "graph"], default="eager",
+                    help="eager: launch every kernel from the host (default; measured fastest); graph: replay a "
+                         "captured HIP graph of the step")
+    ap.add_argument("--lanes", type=int, default=2, choices=[1, 2],
+                    help="streams of the backward pass: 2 = weight branches on a second stream beside the "
+                         "data-gradient chain (default), 1 = everything on one stream")
     ap.add_argument("--cpu-sample-images", type=int, default=32)
     return ap.parse_args()
 
@@ -95,8 +98,9 @@ def main():
     seq = runner.Sequencer(wl, "cuda:0")
     stream = torch.cuda.current_stream()
 
-    # one step = the same 16 launches either way; the graph only removes per-launch host work
-    run_step = seq.capture().replay if args.graph else seq.step
+    # one step = the same kernels either way
+    lanes = args.lanes
+    run_step = seq.capture(lanes).replay if args.launch == "graph" else (lambda: seq.step(lanes=lanes))
     for _ in range(args.warmup):
         run_step()
     torch.cuda.synchronize()
@@ -146,7 +150,7 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": wl.name, "global_batch": n, "blocks": len(blocks),
-                   "launch": "hip_graph" if args.graph else "eager",
+                   "launch": "hip_graph" if args.launch == "graph" else "eager", "backward_lanes": lanes,
                    "flop_per_step": flops, "pct_mfma_peak": round(100 * value / MFMA_BF16_PEAK_TFLOPS, 2)},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,

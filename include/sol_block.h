@@ -90,7 +90,12 @@ SOL_API int sol_block_fwd(const sol_block_desc* desc, const void* x, const void*
  *   dx[n,hi,wi,ci]  = sum_{kh,kw,co} g[n,ho,wo,co] * scale[co] * W[co,kh,kw,ci]   (+ addend)
  *   dW[co,kh,kw,ci] = scale[co] * sum_{n,ho,wo} g[n,ho,wo,co] * x[n,hi,wi,ci]
  *   dshift[co]      = sum g[.,co]          dscale[co] = sum g[.,co] * conv(x,W)[.,co]
- * Nullable: dx (skips the data gradient altogether), dres, dx_addend, dx_addend_mask, dx_mask.
+ * Nullable: dx (skips the data gradient altogether), dres, dx_addend, dx_addend_mask, dx_mask;
+ * dW, dscale and dshift may be NULL together (skips the weight branch: the split weight-gradient
+ * GEMM and its reduction); at least one of dx, dres, dW must be given.  The data branch and the
+ * weight branch read the same inputs and use disjoint parts of the workspace, so a caller may
+ * issue them as two calls on two streams (one with dW = NULL, one with dx = dres = NULL), sharing
+ * one workspace, as long as calls of the same kind are ordered among themselves.
  *   dres            out, [N][Ho][Wo][C_out]: g itself (the gradient of the residual input).
  *   dx_addend       in,  [N][H][W][C_in]: added to dx in the epilogue (shortcut gradients).
  *   dx_addend_mask  in,  same shape as dx_addend: when given, only elements whose mask value

@@ -3,8 +3,6 @@
 #include <stdlib.h>
 #include <string.h>
 
-#include <mutex>
-
 #include "../../include/sol_block.h"
 #include "classes.h"
 #include "launch.h"
@@ -50,41 +48,6 @@ int env_int(const char* name, int fallback) {
     const char* v = getenv(name);
     if (!v || !*v) return fallback;
     return atoi(v);
-}
-
-// The weight-gradient branch of a backward call (split GEMM + reduction) does not depend on the
-// data-gradient branch (weight re-pack + GEMM), and neither fills the chip alone at ResNet sizes.
-// The call therefore forks: the weight branch is enqueued on a library-owned stream that first waits
-// for an event recorded on the caller's stream, and the caller's stream waits for the branch's end
-// event before the call's work counts as done -- seen from the caller, everything stays ordered on
-// the caller's stream.  One lane (stream + two events, default priority) per device, created on the
-// first backward call on that device and kept until the process ends; the mutex makes the
-// record/wait pairs of concurrent host threads atomic.  The fork is off unless SOL_BWD_OVERLAP=1: launched from the host the event traffic costs more than the
-// overlap gains (measured); inside a captured graph it gains a few percent.
-struct SideLane {
-    hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr;
-    int state = 0;                      // 0 untried, 1 ready, -1 creation failed (fork stays off)
-};
-constexpr int kMaxDevices = 64;
-SideLane g_lanes[kMaxDevices];
-std::mutex g_lane_mutex;
-
-// Caller holds g_lane_mutex.
-SideLane* side_lane() {
-    int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
-    SideLane& l = g_lanes[dev];
-    if (l.state == 0) {
-        l.state = -1;
-        if (hipStreamCreateWithFlags(&l.stream, hipStreamNonBlocking) == hipSuccess &&
-            hipEventCreateWithFlags(&l.fork, hipEventDisableTiming) == hipSuccess &&
-            hipEventCreateWithFlags(&l.join, hipEventDisableTiming) == hipSuccess)
-            l.state = 1;
-        else
-            (void)hipGetLastError();
-    }
-    return l.state == 1 ? &l : nullptr;
 }
 
 // Largest tile that still yields about one workgroup per compute unit; small problems fall
@@ -362,7 +325,9 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
     Geometry g;
     if (int e = check_desc(desc, &g); e != SOL_OK) return e;
     const bool relu = (desc->flags & SOL_RELU) != 0;
-    if (!dy || !x || !W || !dW || !dscale || !dshift || !scale) return SOL_ERR_NULL;
+    if (!dy || !x || !W || !scale) return SOL_ERR_NULL;
+    if (dW ? (!dscale || !dshift) : (dscale || dshift)) return SOL_ERR_NULL;   // the three come together
+    if (!dW && !dx && !dres) return SOL_ERR_NULL;                              // nothing to compute
     if (relu && !y) return SOL_ERR_NULL;
     if (dx_addend_mask && !dx_addend) return SOL_ERR_NULL;
     if (misaligned(dy) || misaligned(x) || misaligned(W) || misaligned(y) || misaligned(dx) || misaligned(dW) ||
@@ -459,23 +424,9 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
         return launch_wgrad_reduce(rp, st) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
     };
 
-    if ((dx || dres) && env_int("SOL_BWD_OVERLAP", 0) != 0) {
-        std::lock_guard<std::mutex> hold(g_lane_mutex);
-        if (SideLane* lane = side_lane()) {
-            if (hipEventRecord(lane->fork, stream) != hipSuccess ||
-                hipStreamWaitEvent(lane->stream, lane->fork, 0) != hipSuccess)
-                return SOL_ERR_LAUNCH;
-            const int ew = weight_branch(lane->stream);
-            // the join is enqueued whatever happened, so the lane never holds work the caller's stream
-            // does not wait for
-            const bool joined = hipEventRecord(lane->join, lane->stream) == hipSuccess;
-            const int ed = data_branch(stream);
-            if (!joined || hipStreamWaitEvent(stream, lane->join, 0) != hipSuccess) return SOL_ERR_LAUNCH;
-            return ew != SOL_OK ? ew : ed;
-        }
-    }
+    // the two branches share only inputs (dy, x, W, scale) and use disjoint parts of the workspace
     if (int e = data_branch(stream); e != SOL_OK) return e;
-    return weight_branch(stream);
+    return dW ? weight_branch(stream) : SOL_OK;
 }
 
 SOL_API int sol_l1_loss_grad(int32_t dtype, const void* y, const void* t, void* dy, int64_t numel, int32_t mask_by_y,

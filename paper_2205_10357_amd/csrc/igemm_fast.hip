@@ -249,11 +249,13 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
         if (nk >= NS - 1) wait_vm_and_lds<(NS - 2) * LPS>();
         else wait_vm_and_lds<0>();
         wg_barrier();
-        read_frags(0, lds, 0);
-        int kt = 0;
-        for (; kt + NS - 1 < nk; ++kt) slice(kt, std::true_type{}, std::true_type{});
-        for (; kt + 1 < nk; ++kt) slice(kt, std::true_type{}, std::false_type{});
-        slice(kt, std::false_type{}, std::false_type{});
+        if (nk > 0) {                // a row class without taps (strided data gradient) has nothing to multiply
+            read_frags(0, lds, 0);
+            int kt = 0;
+            for (; kt + NS - 1 < nk; ++kt) slice(kt, std::true_type{}, std::true_type{});
+            for (; kt + 1 < nk; ++kt) slice(kt, std::true_type{}, std::false_type{});
+            slice(kt, std::false_type{}, std::false_type{});
+        }
     } else {
         // Two stages: one K slice = wait for it, multiply it, and (MORE) request the next one in four
         // parts between the MFMA groups; one barrier at the start of every slice.

@@ -15,6 +15,14 @@ Layer merging across blocks in the backward pass (the paper's grouping of connec
   * shortcut gradients never get a pass of their own: an identity shortcut is added in the
     epilogue of the data gradient that writes the block input's gradient (``dx_addend``), and a
     projection shortcut simply takes the tail block's (masked) gradient as its dy.
+
+Two lanes in the backward pass.  Only the data gradients form a chain (each block's dx is the next
+block's dy); a block's weight branch (weight gradient, its reduction, dscale, dshift) is a leaf that
+needs nothing but that block's dy and x.  At ResNet sizes neither kind of kernel fills the chip
+(a data-gradient GEMM has fewer tiles than there are compute units), so ``backward(lanes=2)``
+issues the weight branches on a second stream that waits, block by block, for the gradient they
+read, and joins the first stream at the end of the step (a few percent faster than one lane,
+measured; a captured graph runs its branches no faster than one lane).
 """
 from __future__ import annotations
 
@@ -91,6 +99,7 @@ class Sequencer:
                                    B.BlockDesc(n, h, w, o.c_in, o.c_out, o.k, o.k, o.stride, o.pad,
                                                self.sol_dtype, B.SOL_RELU), B.SOL_PASS_BWD))
         self.ws = torch.empty((max(ws_bytes, 256),), dtype=torch.uint8, device=self.device)
+        self._side: Optional[torch.cuda.Stream] = None
         self.grads: Dict[int, Dict[str, torch.Tensor]] = {}
         self.dact: Dict[int, torch.Tensor] = {}
         self.target: Optional[torch.Tensor] = None
@@ -181,32 +190,50 @@ class Sequencer:
             calls.append(call)
         self._bwd_calls = calls
 
-    def backward(self, stream=None) -> None:
+    def backward(self, stream=None, lanes: int = 1) -> None:
+        if lanes == 1:
+            for c in self._bwd_calls:
+                o = c["op"]
+                p, g = self.params[o.layer], self.grads[o.layer]
+                B.sol_block_bwd(c["desc"], c["dy"], self.act[o.inp], p["W"], None, c["dx"], g["dW"], g["dscale"],
+                                g["dshift"], p["scale"], None, c["addend"], None, c["dx_mask"], self.ws, None, stream)
+            return
+        main = stream if stream is not None else torch.cuda.current_stream(self.device)
+        if self._side is None:
+            self._side = torch.cuda.Stream(device=self.device)       # default priority
+        side = self._side
         for c in self._bwd_calls:
             o = c["op"]
             p, g = self.params[o.layer], self.grads[o.layer]
-            B.sol_block_bwd(c["desc"], c["dy"], self.act[o.inp], p["W"], None, c["dx"], g["dW"], g["dscale"],
-                            g["dshift"], p["scale"], None, c["addend"], None, c["dx_mask"], self.ws, None, stream)
+            # dy of this block is complete on the main lane here (loss kernel or the previous data gradient)
+            side.wait_stream(main)
+            B.sol_block_bwd(c["desc"], c["dy"], self.act[o.inp], p["W"], None, None, g["dW"], g["dscale"],
+                            g["dshift"], p["scale"], None, None, None, None, self.ws, None, side)
+            if c["dx"] is not None:
+                B.sol_block_bwd(c["desc"], c["dy"], self.act[o.inp], p["W"], None, c["dx"], None, None, None,
+                                p["scale"], None, c["addend"], None, c["dx_mask"], self.ws, None, main)
+        main.wait_stream(side)
 
-    def capture(self) -> "torch.cuda.CUDAGraph":
-        """Record one step (all launches, in order) into a HIP graph; ``graph.replay()`` then runs it
-        without per-launch host work.  The library itself allocates nothing and enqueues only on the
-        stream it is given, so a step is capturable as it is (no memsets are recorded)."""
-        side = torch.cuda.Stream(device=self.device)
-        side.wait_stream(torch.cuda.current_stream(self.device))
-        with torch.cuda.stream(side):
-            self.step()                      # first use of every kernel happens outside the capture
-        torch.cuda.current_stream(self.device).wait_stream(side)
+    def capture(self, lanes: int = 2) -> "torch.cuda.CUDAGraph":
+        """Record one step into a HIP graph; ``graph.replay()`` then runs it without per-launch host
+        work, the weight branches of the backward pass as parallel branches of the graph (lanes=2).
+        The library itself allocates nothing and enqueues only on the stream it is given, so a step is
+        capturable as it is (no memsets are recorded)."""
+        warm = torch.cuda.Stream(device=self.device)
+        warm.wait_stream(torch.cuda.current_stream(self.device))
+        with torch.cuda.stream(warm):
+            self.step(lanes=lanes)           # first use of every kernel happens outside the capture
+        torch.cuda.current_stream(self.device).wait_stream(warm)
         torch.cuda.synchronize(self.device)
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
-            self.step()
+            self.step(lanes=lanes)
         self.graph = graph
         return graph
 
-    def step(self, stream=None) -> None:
+    def step(self, stream=None, lanes: int = 1) -> None:
         """One pass of the whole path: forward, and for training the loss gradient and backward."""
         self.forward(stream)
         if self.wl.train:
             self.loss_grad(stream)
-            self.backward(stream)
+            self.backward(stream, lanes)

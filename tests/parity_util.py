@@ -52,7 +52,7 @@ def make_case(seed, N, H, W, C_in, C_out, K, stride, pad, bf16=True, relu=True, 
 
 
 def gpu_block(case, need_dx=True, want_dres=False, addend=None, addend_mask=None, guard=True, accumulate=False,
-              dw_init=None, dx_mask=None, premasked=False):
+              dw_init=None, dx_mask=None, premasked=False, two_calls=False):
     """Forward, L1 gradient and backward of one block on the GPU.  Returns host arrays in the
     checker's layout plus the raw device tensors."""
     d, bf16 = case["d"], case["bf16"]
@@ -94,7 +94,18 @@ def gpu_block(case, need_dx=True, want_dres=False, addend=None, addend_mask=None
     if premasked:           # gradient already masked by this block's ReLU: backward without flag and y
         desc = B.BlockDesc(d.N, d.H, d.W, d.C_in, d.C_out, d.KH, d.KW, d.stride, d.pad, dt,
                            flags & ~B.SOL_RELU)
-    B.sol_block_bwd(desc, dy, x, w, None if premasked else y, dx, dW, dscale, dshift, scale, dres, ad, am, dxm, ws, ws_bytes)
+    ymask = None if premasked else y
+    if two_calls:           # weight branch on a second stream, data branch on the first, one shared workspace
+        main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+        side.wait_stream(main)
+        B.sol_block_bwd(desc, dy, x, w, ymask, None, dW, dscale, dshift, scale, None, None, None, None, ws, ws_bytes,
+                        stream=side)
+        if need_dx or want_dres:
+            B.sol_block_bwd(desc, dy, x, w, ymask, dx, None, None, None, scale, dres, ad, am, dxm, ws, ws_bytes,
+                            stream=main)
+        main.wait_stream(side)
+    else:
+        B.sol_block_bwd(desc, dy, x, w, ymask, dx, dW, dscale, dshift, scale, dres, ad, am, dxm, ws, ws_bytes)
     torch.cuda.synchronize()
 
     if guard:

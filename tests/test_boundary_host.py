@@ -62,6 +62,13 @@ def test_pointer_validation():
     # ReLU block needs y for the mask; a block without ReLU does not
     assert B.sol_block_bwd(d, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None, None, FAKE, 1 << 40,
                            stream=0, check=False) == -1
+    # dW, dscale, dshift come together; with none of them some other output must be asked for
+    assert B.sol_block_bwd(d, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, None, None, None, None, FAKE, 1 << 40,
+                           stream=0, check=False) == -1
+    assert B.sol_block_bwd(d, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, None, None, None, None, FAKE, 1 << 40,
+                           stream=0, check=False) == -1
+    assert B.sol_block_bwd(d, FAKE, FAKE, FAKE, FAKE, None, None, None, None, FAKE, None, None, None, None, FAKE, 1 << 40,
+                           stream=0, check=False) == -1
     # addend mask without addend
     assert B.sol_block_bwd(d, *args, None, None, FAKE, None, FAKE, 1 << 40, stream=0, check=False) == -1
     # workspace missing / too small

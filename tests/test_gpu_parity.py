@@ -87,6 +87,7 @@ def test_bf16_resnet50_layer_shapes(spec):
     dict(N=1, H=13, W=11, C_in=12, C_out=20, K=3, stride=1, pad=1),           # channels not a multiple of 8
     dict(N=2, H=9, W=11, C_in=24, C_out=16, K=3, stride=2, pad=1),            # odd sizes under stride 2
     dict(N=2, H=7, W=9, C_in=16, C_out=40, K=1, stride=2, pad=0, relu=False), # 1x1/s2: 3 of 4 pixel classes see no tap
+    dict(N=2, H=14, W=14, C_in=64, C_out=512, K=1, stride=2, pad=0, relu=False),  # same, long reduction (deep copy ring)
     dict(N=1, H=12, W=12, C_in=3, C_out=8, K=7, stride=2, pad=3),             # stem-like with a data gradient
     dict(N=1, H=33, W=31, C_in=64, C_out=136, K=3, stride=1, pad=1),          # ragged in pixels and channels
     dict(N=2, H=6, W=6, C_in=8, C_out=8, K=5, stride=1, pad=2),               # 5x5
@@ -149,6 +150,22 @@ def test_premasked_gradient_and_dx_mask(shape):
     ad = snap(r.standard_normal(case["x"].shape).astype(np.float32))
     got = pu.gpu_block(case, addend=ad, dx_mask=dxm, premasked=True)
     show(f"premasked {shape}", pu.check_block(case, got, addend=ad, dx_mask=dxm, premasked=True))
+
+
+@pytest.mark.parametrize("shape", [
+    dict(N=4, H=14, W=14, C_in=256, C_out=64, K=3, stride=1, pad=1),                  # pipelined kernels
+    dict(N=2, H=15, W=13, C_in=24, C_out=40, K=3, stride=2, pad=1),                   # general kernels
+    dict(N=1, H=8, W=8, C_in=8, C_out=8, K=3, stride=1, pad=1, bf16=False),           # fp32 path
+])
+def test_data_and_weight_branch_as_two_calls(shape):
+    """Backward issued as two calls on two streams (dW = NULL / dx = NULL) sharing one workspace: same bits as
+    the single call, and parity with the checker."""
+    case = pu.make_case(31, res=True, **shape)
+    one = pu.gpu_block(case, want_dres=True)
+    two = pu.gpu_block(case, want_dres=True, two_calls=True)
+    for k in ("dx", "dW", "dscale", "dshift", "dres"):
+        assert np.array_equal(one[k], two[k]), k
+    show(f"two calls {shape}", pu.check_block(case, two))
 
 
 def test_runs_are_bitwise_reproducible():

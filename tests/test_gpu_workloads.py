@@ -238,9 +238,33 @@ def test_stage2_full_size_sampled():
                   dw_layers=("s2.b0.conv2", "s2.b0.proj", "s2.b0.conv3", "s2.b2.conv1"), n_dw=48)
 
 
+def test_two_lane_backward_matches_one_lane():
+    """Weight branches on a second stream (block by block behind the gradient they read): same bits."""
+    w = wl.stage2_train_bf16(n=2, hw=14)
+    seq = runner.Sequencer(w, "cuda:0")
+    seq.step()
+    torch.cuda.synchronize()
+    ref = {k: {n: t.clone() for n, t in v.items()} for k, v in seq.grads.items()}
+    ref_d = {k: v.clone() for k, v in seq.dact.items()}
+    for it in range(2):
+        for v in seq.grads.values():
+            for t in v.values():
+                t.fill_(3.0)
+        torch.cuda.synchronize()
+        seq.step(lanes=2)
+        torch.cuda.synchronize()
+        for k, v in ref.items():
+            for n, t in v.items():
+                assert torch.equal(seq.grads[k][n], t), (it, k, n)
+        for c in seq._bwd_calls:
+            if c["dx"] is not None:
+                k = next(i for i, t in seq.dact.items() if t is c["dx"])
+                assert torch.equal(seq.dact[k], ref_d[k]), (it, k)
+
+
 def test_graph_replays_match_eager():
-    """A captured step replayed several times, with eager work and synchronisations in between, gives the
-    eager result bit for bit every time."""
+    """A captured step (two lanes: weight branches as parallel branches of the graph) replayed several times,
+    with eager work and synchronisations in between, gives the eager one-lane result bit for bit every time."""
     w = wl.bottleneck14_bf16(n=8)
     seq = runner.Sequencer(w, "cuda:0")
     seq.step()
