@@ -119,6 +119,8 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, hipStream_t stre
         const bool lin_out = rc.oh_mul == 1 && rc.ow_mul == 1 && rc.oh_off == 0 && rc.ow_off == 0 &&
                              rc.Rh == p.Hout && rc.Rw == p.Wout;
         rc.linear = (lin_src ? 1 : 0) | (lin_out ? 2 : 0);
+        rc.div_img = make_fast_div((uint32_t)(rc.Rh * rc.Rw));
+        rc.div_rw = make_fast_div((uint32_t)rc.Rw);
         p.cls[c].tile_begin = tiles_p;
         tiles_p += (int)((rows[c] + bp - 1) / bp);
     }

@@ -89,6 +89,25 @@ __device__ __forceinline__ void wg_barrier() {
     asm volatile("" ::: "memory");
 }
 
+// Forces a launch parameter into a scalar register at this point.  Kernel arguments live in memory and
+// the compiler fetches each one where it is first used, waiting for every fetch separately; a kernel
+// that names all of its parameters here, at the top, pays one memory round trip for the batch
+// instead of one per use site (each costs several hundred nanoseconds on a cold scalar cache).
+#define SOL_FETCH_NOW_8(a, b, c, d, e, f, g, h) \
+    asm volatile("" ::"s"(a), "s"(b), "s"(c), "s"(d), "s"(e), "s"(f), "s"(g), "s"(h))
+
+// ---- division by a launch-invariant divisor (n < 2^31): q = (mulhi(n, magic) + n) >> shift ------
+struct FastDiv {
+    uint32_t magic, shift;
+};
+inline FastDiv make_fast_div(uint32_t d) {
+    uint32_t s = 0;
+    while ((1ull << s) < d) ++s;
+    const uint64_t m = ((1ull << 32) * ((1ull << s) - d)) / d + 1;
+    return FastDiv{(uint32_t)m, s};
+}
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, FastDiv d) { return (__umulhi(n, d.magic) + n) >> d.shift; }
+
 // ---- implicit-GEMM launch parameters -----------------------------------------------------
 // One "row class" describes which GEMM rows (pixels) a group of workgroups produces and how a
 // row and a filter tap map to a source pixel.  The forward pass has one class; the data
@@ -107,6 +126,7 @@ struct RowClass {
     int linear;             // bit 0: source pixel index == row (1x1, stride 1, no padding);
                             // bit 1: output pixel index == row (all rows of the output, in order)
     long long b_off;        // element offset of this class' weight matrix [Nc][Th*Tw*Cs]
+    FastDiv div_img, div_rw;// divisors Rh*Rw and Rw (row index -> image, row and column in the image)
 };
 
 constexpr int kMaxClasses = 4;
@@ -131,18 +151,6 @@ struct IgemmParams {
     int total_tiles;
     RowClass cls[kMaxClasses];
 };
-
-// ---- division by a launch-invariant divisor (n < 2^31): q = (mulhi(n, magic) + n) >> shift ------
-struct FastDiv {
-    uint32_t magic, shift;
-};
-inline FastDiv make_fast_div(uint32_t d) {
-    uint32_t s = 0;
-    while ((1ull << s) < d) ++s;
-    const uint64_t m = ((1ull << 32) * ((1ull << s) - d)) / d + 1;
-    return FastDiv{(uint32_t)m, s};
-}
-__device__ __forceinline__ uint32_t fast_div(uint32_t n, FastDiv d) { return (__umulhi(n, d.magic) + n) >> d.shift; }
 
 // LDS read with transpose (16-bit elements): within each group of 16 lanes, the 16 x 8-byte
 // pieces the lanes address form a 4 x 16 matrix (4 consecutive lanes = one row of 16 elements);

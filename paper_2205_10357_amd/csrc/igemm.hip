@@ -61,8 +61,8 @@ __global__ __launch_bounds__(256) void igemm_bf16_kernel(const IgemmParams p) {
     for (int i = 0; i < AP; ++i) {
         const int r = row0 + r0 + 32 * i;
         if (r < rc.rows) {
-            const int n = r / img_rows, rem = r - n * img_rows;
-            const int rh = rem / rc.Rw, rw = rem - rh * rc.Rw;
+            const int n = (int)fast_div((uint32_t)r, rc.div_img), rem = r - n * img_rows;
+            const int rh = (int)fast_div((uint32_t)rem, rc.div_rw), rw = rem - rh * rc.Rw;
             h0[i] = rh * rc.h_mul + rc.h_off;
             w0[i] = rw * rc.w_mul + rc.w_off;
             img[i] = n * p.Hs * p.Ws * p.Cs;
@@ -231,8 +231,8 @@ __global__ __launch_bounds__(256) void igemm_bf16_kernel(const IgemmParams p) {
     for (int j = 0; j < TP; ++j) {
         const int r = row0 + wp * (BP / WP) + j * 32 + (lane & 31);
         if (r >= rc.rows) continue;
-        const int n = r / img_rows, rem = r - n * img_rows;
-        const int rh = rem / rc.Rw, rw = rem - rh * rc.Rw;
+        const int n = (int)fast_div((uint32_t)r, rc.div_img), rem = r - n * img_rows;
+        const int rh = (int)fast_div((uint32_t)rem, rc.div_rw), rw = rem - rh * rc.Rw;
         const long long opix = ((long long)n * p.Hout + (rh * rc.oh_mul + rc.oh_off)) * p.Wout +
                                (rw * rc.ow_mul + rc.ow_off);
         const long long obase = opix * p.Nc;

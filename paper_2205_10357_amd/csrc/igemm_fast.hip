@@ -42,14 +42,25 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // wave-uniform: keeps LDS bases scalar
-    const int bid = fast_xcd_remap(blockIdx.x, gridDim.x);
+    // all launch parameters in one batch of scalar loads; with one row class (forward, stride-1 data
+    // gradient) the class is at a fixed place and belongs to the batch, else it costs a second round trip
+    RowClass rc = p.cls[0];
+    SOL_FETCH_NOW_8(p.src, p.wmat, p.out, p.scale, p.shift, p.addend, p.addend_mask, p.out_mask);
+    SOL_FETCH_NOW_8(p.src_bytes, p.Hs, p.Ws, p.Cs, p.Nc, p.Hout, p.Wout, p.relu);
+    SOL_FETCH_NOW_8(p.ncls, p.tiles_c, rc.rows, rc.Rh, rc.Rw, rc.h_mul, rc.h_off, rc.w_mul);
+    SOL_FETCH_NOW_8(rc.w_off, rc.Th, rc.Tw, rc.tap_step, rc.oh_mul, rc.oh_off, rc.ow_mul, rc.ow_off);
+    SOL_FETCH_NOW_8(rc.tile_begin, rc.linear, rc.b_off, rc.div_img.magic, rc.div_img.shift, rc.div_rw.magic,
+                    rc.div_rw.shift, p.total_tiles);
+    const int bid = fast_xcd_remap(blockIdx.x, p.total_tiles);     // the launch has total_tiles workgroups
     const int tc = bid % p.tiles_c;
     int tp = bid / p.tiles_c;
-    int cidx = 0;
+    if (p.ncls > 1) {
+        int cidx = 0;
 #pragma unroll
-    for (int i = 1; i < kMaxClasses; ++i)
-        if (i < p.ncls && tp >= p.cls[i].tile_begin) cidx = i;
-    const RowClass rc = p.cls[cidx];
+        for (int i = 1; i < kMaxClasses; ++i)
+            if (i < p.ncls && tp >= p.cls[i].tile_begin) cidx = i;
+        rc = p.cls[cidx];
+    }
     tp -= rc.tile_begin;
     const int row0 = tp * BP, ch0 = tc * BC;
     const int cpt = p.Cs >> 6;                         // slices per tap
@@ -95,18 +106,29 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
                 rowb[i] = (unsigned)(r * p.Cs + cl * 8) * 2u;
                 badtap[i] = 0xfffffffeu;
             } else {
-                const int n = r / img_rows, rem = r - n * img_rows;
-                const int rh = rem / rc.Rw, rw = rem - rh * rc.Rw;
+                const int n = (int)fast_div((uint32_t)r, rc.div_img), rem = r - n * img_rows;
+                const int rh = (int)fast_div((uint32_t)rem, rc.div_rw), rw = rem - rh * rc.Rw;
                 const int h0 = rh * rc.h_mul + rc.h_off, w0 = rw * rc.w_mul + rc.w_off;
                 rowb[i] = (unsigned)(((n * p.Hs + h0) * p.Ws + w0) * p.Cs + cl * 8) * 2u;
-                unsigned hbad = 0u, wbad = 0u;
-                for (int th = 0; th < rc.Th; ++th)
-                    if ((unsigned)(h0 + th * rc.tap_step) >= (unsigned)p.Hs) hbad |= 1u << th;
-                for (int tw = 0; tw < rc.Tw; ++tw)
-                    if ((unsigned)(w0 + tw * rc.tap_step) >= (unsigned)p.Ws) wbad |= 1u << tw;
+                // taps th with 0 <= h0 + th * tap_step < Hs form one interval [lo, hi] (tap_step = +1 or -1)
+                auto bad_taps = [&](int v0, int extent, int taps) -> unsigned {
+                    const int lo = rc.tap_step > 0 ? -v0 : v0 - extent + 1;
+                    const int hi = rc.tap_step > 0 ? extent - 1 - v0 : v0;
+                    const int l = lo > 0 ? lo : 0, h = hi < taps - 1 ? hi : taps - 1;
+                    const unsigned long long all = (1ull << taps) - 1ull;
+                    const unsigned long long good = h >= l ? ((1ull << (h + 1)) - 1ull) & ~((1ull << l) - 1ull) : 0ull;
+                    return (unsigned)(all & ~good);
+                };
+                const unsigned hbad = bad_taps(h0, p.Hs, rc.Th), wbad = bad_taps(w0, p.Ws, rc.Tw);
+                const unsigned wall = (unsigned)((1ull << rc.Tw) - 1ull);
                 unsigned bad = 0u;
-                for (int th = 0; th < rc.Th; ++th)
-                    bad |= (((hbad >> th) & 1u) ? ((1u << rc.Tw) - 1u) : wbad) << (th * rc.Tw);
+                if (rc.Th <= 8) {
+#pragma unroll
+                    for (int th = 0; th < 8; ++th)
+                        if (th < rc.Th) bad |= (((hbad >> th) & 1u) ? wall : wbad) << (th * rc.Tw);
+                } else {
+                    for (int th = 0; th < rc.Th; ++th) bad |= (((hbad >> th) & 1u) ? wall : wbad) << (th * rc.Tw);
+                }
                 badtap[i] = bad;
             }
         }
@@ -316,8 +338,8 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
             const int r = row0 + pr0 + ps * RPP;
             ovalid[ps] = ch_ok && r < rc.rows;
             const int rr = ovalid[ps] ? r : 0;
-            const int n = rr / img_rows, rem = rr - n * img_rows;
-            const int rh = rem / rc.Rw, rw = rem - rh * rc.Rw;
+            const int n = (int)fast_div((uint32_t)rr, rc.div_img), rem = rr - n * img_rows;
+            const int rh = (int)fast_div((uint32_t)rem, rc.div_rw), rw = rem - rh * rc.Rw;
             const long long opix = ((long long)n * p.Hout + (rh * rc.oh_mul + rc.oh_off)) * p.Wout +
                                    (rw * rc.ow_mul + rc.ow_off);
             oofs[ps] = opix * p.Nc + ch;
