@@ -6,6 +6,7 @@
 #include "../../include/sol_block.h"
 #include "classes.h"
 #include "launch.h"
+#include "pack_tile.h"
 
 namespace sol {
 namespace {
@@ -365,17 +366,22 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
         return p;
     };
 
-    // ---- data branch: shortcut gradient, weight re-pack, data-gradient GEMM (caller's stream) ----
+    // The re-pack of the weights for the data gradient rides along with the weight-gradient launch (as extra
+    // workgroups) when one call computes both branches with the pipelined kernels; else it is a launch of its own.
+    const bool bf16_vec = desc->dtype == SOL_BF16 && (desc->C_in % 8) == 0 && (desc->C_out % 8) == 0;
+    const bool wgrad_pipelined = bf16_vec && !relu && env_int("SOL_WGRAD_FAST", 1) != 0;
+    PackParams pk{(const bf16_t*)W, scale, (bf16_t*)(wsb + plan.wpack_off), desc->C_in, desc->C_out, desc->KH,
+                  desc->KW, desc->stride, desc->pad};
+    const bool pack_rides = dx && dW && wgrad_pipelined && pack_tiled_ok(pk) && env_int("SOL_PACK_FUSED", 1) != 0;
+
+    // ---- data branch: shortcut gradient, weight re-pack, data-gradient GEMM ----
     auto data_branch = [&](hipStream_t st) -> int {
         if (dres && launch_masked_copy(desc->dtype, dy, ymask, dres, g.y_elems, st) != hipSuccess)
             return SOL_ERR_LAUNCH;
         if (!dx) return SOL_OK;
         if (desc->dtype == SOL_BF16) {
-            bf16_t* wpack = (bf16_t*)(wsb + plan.wpack_off);
-            PackParams pk{(const bf16_t*)W, scale, wpack, desc->C_in, desc->C_out, desc->KH, desc->KW,
-                          desc->stride, desc->pad};
-            if (launch_pack_dgrad_weights(pk, st) != hipSuccess) return SOL_ERR_LAUNCH;
-            return dgrad_bf16(desc, g, dy, y, wpack, dx, dx_addend, dx_addend_mask, dx_mask, st);
+            if (!pack_rides && launch_pack_dgrad_weights(pk, st) != hipSuccess) return SOL_ERR_LAUNCH;
+            return dgrad_bf16(desc, g, dy, y, pk.out, dx, dx_addend, dx_addend_mask, dx_mask, st);
         }
         DirectParams p = direct_params();
         return launch_direct_dgrad_f32(p, st) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
@@ -397,9 +403,11 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
             wp.tiles_k = plan.tiles_k; wp.tiles_c = plan.tiles_c;
             wp.div_howo = make_fast_div((uint32_t)(g.Ho * g.Wo));
             wp.div_wo = make_fast_div((uint32_t)g.Wo);
-            const bool vec = (desc->C_in % 8) == 0 && (desc->C_out % 8) == 0;
+            wp.pack = pk;
+            wp.pack_blocks = pack_rides ? pack_tile_count(pk) : 0;
+            const bool vec = bf16_vec;
             // pipelined kernel when dy needs no mask; SOL_WGRAD_FAST=0 forces the general kernel
-            if (vec && !relu && env_int("SOL_WGRAD_FAST", 1) != 0) {
+            if (wgrad_pipelined) {
                 int stages = env_int("SOL_WGRAD_STAGES", 2);
                 if (stages < 2 || stages > 4) stages = 3;
                 if (launch_wgrad_fast(wp, stages, st) != hipSuccess) return SOL_ERR_LAUNCH;
@@ -427,6 +435,10 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
     };
 
     // the two branches share only inputs (dy, x, W, scale) and use disjoint parts of the workspace
+    if (pack_rides) {
+        if (int e = weight_branch(stream); e != SOL_OK) return e;
+        return data_branch(stream);
+    }
     if (int e = data_branch(stream); e != SOL_OK) return e;
     return dW ? weight_branch(stream) : SOL_OK;
 }

@@ -93,8 +93,10 @@ __device__ __forceinline__ void wg_barrier() {
 // the compiler fetches each one where it is first used, waiting for every fetch separately; a kernel
 // that names all of its parameters here, at the top, pays one memory round trip for the batch
 // instead of one per use site (each costs several hundred nanoseconds on a cold scalar cache).
+#ifndef SOL_FETCH_NOW_8
 #define SOL_FETCH_NOW_8(a, b, c, d, e, f, g, h) \
     asm volatile("" ::"s"(a), "s"(b), "s"(c), "s"(d), "s"(e), "s"(f), "s"(g), "s"(h))
+#endif
 
 // ---- division by a launch-invariant divisor (n < 2^31): q = (mulhi(n, magic) + n) >> shift ------
 struct FastDiv {
@@ -162,6 +164,13 @@ __device__ __forceinline__ uintx2 lds_read_tr_b64(const void* lds_addr) {
     return __builtin_bit_cast(uintx2, v);
 }
 
+struct PackParams {            // scale-folded, per-row-class transposed weights for the data gradient
+    const bf16_t* W;           // [C_out][KH][KW][C_in]
+    const float* scale;
+    bf16_t* out;               // per class: [C_in][Th*Tw*C_out]
+    int C_in, C_out, KH, KW, stride, pad;
+};
+
 // ---- weight-gradient launch parameters ---------------------------------------------------
 struct WgradParams {
     const bf16_t* dy;           // [M][C_out]
@@ -176,6 +185,10 @@ struct WgradParams {
     int m_per_split;            // multiple of the reduction tile
     int tiles_k, tiles_c;
     FastDiv div_howo, div_wo;   // divisors Ho*Wo and Wo
+    // pipelined kernel only: pack_blocks > 0 appends that many workgroups to the launch, which re-pack the
+    // weights for the data gradient of the same block (one 64 x 64 tile each) instead of multiplying
+    PackParams pack;
+    int pack_blocks;
 };
 
 struct ReduceParams {

@@ -2,6 +2,7 @@
 // gradient, the masked gradient copy (dres), the L1-loss gradient and the stem max-pool.
 #include "launch.h"
 #include "classes.h"
+#include "pack_tile.h"
 
 namespace sol {
 
@@ -27,49 +28,10 @@ __global__ __launch_bounds__(256) void pack_dgrad_weights_kernel(const PackParam
     p.out[off + ((long long)ci * Th * Tw + (jh * Tw + jw)) * p.C_out + co] = f32_to_bf16(p.scale[co] * w);
 }
 
-// Same re-packing for channel counts that are multiples of 64: one workgroup per (tap, 64 co, 64 ci)
-// tile, transposed through LDS so that both the reads (ci contiguous) and the writes (co contiguous)
-// are 16-byte pieces of 128-byte rows.
+// Same re-packing for channel counts that are multiples of 64: one workgroup per (tap, 64 co, 64 ci) tile.
 __global__ __launch_bounds__(256) void pack_dgrad_weights_tiled_kernel(const PackParams p) {
-    constexpr int PITCH = 72;                          // bf16 elements per LDS row (144 bytes, 16-byte aligned)
-    __shared__ __align__(16) bf16_t tile[64 * PITCH];  // [ci][co]
-    const int tid = threadIdx.x;
-    const int tiles_ci = p.C_in >> 6, tiles_co = p.C_out >> 6;
-    int b = blockIdx.x;
-    const int tci = b % tiles_ci;
-    b /= tiles_ci;
-    const int tco = b % tiles_co;
-    const int tap = b / tiles_co;
-    const int kh = tap / p.KW, kw = tap - kh * p.KW;
-    const int co0 = tco * 64, ci0 = tci * 64;
-    const int c8 = tid & 7, r0 = tid >> 3;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int co = co0 + r0 + 32 * i;
-        const float sc = p.scale[co];
-        const uintx4 v = *reinterpret_cast<const uintx4*>(p.W + (((long long)co * p.KH + kh) * p.KW + kw) * p.C_in +
-                                                           ci0 + c8 * 8);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const uint32_t pk = pack_bf16x2(sc * __uint_as_float(v[e] << 16), sc * __uint_as_float(v[e] & 0xffff0000u));
-            tile[(c8 * 8 + 2 * e) * PITCH + r0 + 32 * i] = (bf16_t)(pk & 0xffffu);
-            tile[(c8 * 8 + 2 * e + 1) * PITCH + r0 + 32 * i] = (bf16_t)(pk >> 16);
-        }
-    }
-    __syncthreads();
-    const int s = p.stride;
-    const int ph = ((kh - p.pad) % s + s) % s, pw = ((kw - p.pad) % s + s) % s;
-    int fh, fw;
-    const int Th = class_taps(p.KH, s, p.pad, ph, &fh), Tw = class_taps(p.KW, s, p.pad, pw, &fw);
-    const long long off = class_weight_offset(p.C_in, p.C_out, p.KH, p.KW, s, p.pad, ph, pw);
-    const int jh = (kh - fh) / s, jw = (kw - fw) / s;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int cil = r0 + 32 * i;
-        const uintx4 v = *reinterpret_cast<const uintx4*>(&tile[cil * PITCH + c8 * 8]);
-        *reinterpret_cast<uintx4*>(p.out + off + ((long long)(ci0 + cil) * Th * Tw + (jh * Tw + jw)) * p.C_out + co0 +
-                                   c8 * 8) = v;
-    }
+    __shared__ __align__(16) bf16_t tile[64 * kPackTilePitch];
+    pack_dgrad_weights_tile(p, (int)blockIdx.x, tile);
 }
 
 template <typename T>
@@ -153,7 +115,7 @@ static inline unsigned blocks_for(long long total) { return (unsigned)((total + 
 hipError_t launch_pack_dgrad_weights(const PackParams& p, hipStream_t s) {
     const long long total = (long long)p.C_out * p.KH * p.KW * p.C_in;
     if ((p.C_in & 63) == 0 && (p.C_out & 63) == 0)
-        hipLaunchKernelGGL(pack_dgrad_weights_tiled_kernel, dim3((unsigned)(total >> 12)), dim3(256), 0, s, p);
+        hipLaunchKernelGGL(pack_dgrad_weights_tiled_kernel, dim3((unsigned)pack_tile_count(p)), dim3(256), 0, s, p);
     else
         hipLaunchKernelGGL(pack_dgrad_weights_kernel, dim3(blocks_for(total)), dim3(256), 0, s, p);
     return hipGetLastError();

@@ -35,12 +35,6 @@ struct DirectParams {
     int N, H, W_, C_in, C_out, KH, KW, stride, pad, Ho, Wo, relu;
 };
 
-struct PackParams {            // scale-folded, per-row-class transposed weights for the data gradient
-    const bf16_t* W;           // [C_out][KH][KW][C_in]
-    const float* scale;
-    bf16_t* out;               // per class: [C_in][Th*Tw*C_out]
-    int C_in, C_out, KH, KW, stride, pad;
-};
 
 hipError_t launch_igemm(const IgemmParams& p, int tile, bool vec, bool mask, hipStream_t stream);
 void igemm_tile_shape(int tile, int* bp, int* bc);

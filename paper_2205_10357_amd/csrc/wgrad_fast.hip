@@ -18,6 +18,7 @@
 #include <type_traits>
 
 #include "launch.h"
+#include "pack_tile.h"
 #include <sol_lds_tr.h>
 
 namespace sol {
@@ -45,8 +46,13 @@ __global__ __launch_bounds__(256) void wgrad_fast_kernel(const WgradParams p) {
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // wave-uniform: keeps LDS bases scalar
-    const int bid = wgf_xcd_remap(blockIdx.x, gridDim.x);
     const int tiles = p.tiles_k * p.tiles_c;
+    const int nwg = tiles * p.splits;         // workgroups that multiply; the launch may carry re-pack workgroups after them
+    if ((int)blockIdx.x >= nwg) {
+        pack_dgrad_weights_tile(p.pack, (int)blockIdx.x - nwg, reinterpret_cast<bf16_t*>(lds));
+        return;
+    }
+    const int bid = wgf_xcd_remap(blockIdx.x, nwg);
     const int split = bid / tiles;
     const int t = bid - split * tiles;
     const int tk = t % p.tiles_k, tcn = t / p.tiles_k;
@@ -268,7 +274,7 @@ static hipError_t launch_wgf(const WgradParams& p, hipStream_t stream) {
     auto kern = wgrad_fast_kernel<NS, LINEAR>;
     static std::atomic<size_t> granted{0};
     if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), smem, granted); e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(p.tiles_k * p.tiles_c * p.splits), dim3(256), smem, stream, p);
+    hipLaunchKernelGGL(kern, dim3(p.tiles_k * p.tiles_c * p.splits + p.pack_blocks), dim3(256), smem, stream, p);
     return hipGetLastError();
 }
 
