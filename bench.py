@@ -37,10 +37,14 @@ def parse():
     ap.add_argument("--launch", choices=["eager", "graph"], default="eager",
                     help="eager: launch every kernel from the host (default; measured fastest); graph: replay a "
                          "captured HIP graph of the step")
-    ap.add_argument("--lanes", type=int, default=2, choices=[1, 2],
-                    help="streams of the backward pass: 2 = weight branches on a second stream beside the "
-                         "data-gradient chain (default), 1 = everything on one stream")
+    ap.add_argument("--lanes", type=int, default=1, choices=[1, 2],
+                    help="streams of the backward pass: 1 = one call per block on one stream (default; the weight "
+                         "re-pack then rides along with the weight-gradient launch), 2 = weight branches on a second "
+                         "stream beside the data-gradient chain (measured: no faster)")
     ap.add_argument("--cpu-sample-images", type=int, default=32)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run three plain device copies of 256 MiB (torch's copy kernel): under a counter "
+                         "profile their FETCH_SIZE / WRITE_SIZE readings give the scale of those counters")
     return ap.parse_args()
 
 
@@ -97,6 +101,14 @@ def main():
     torch.cuda.set_device(0)
     seq = runner.Sequencer(wl, "cuda:0")
     stream = torch.cuda.current_stream()
+
+    if args.copy_calibration:
+        a = torch.ones(64 << 20, dtype=torch.float32, device="cuda:0")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
 
     # one step = the same kernels either way
     lanes = args.lanes

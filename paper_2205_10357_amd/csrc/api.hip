@@ -151,7 +151,8 @@ BwdPlan plan_bwd(const sol_block_desc* d, const Geometry& g) {
         const long long max_splits = (g.M + 127) / 128;
         long long want = env_int("SOL_WGRAD_SPLITS", 0);
         if (want <= 0) {
-            want = (512 + tiles - 1) / tiles;
+            const long long target = env_int("SOL_WGRAD_TARGET", 384);
+            want = (target + tiles - 1) / tiles;
             // keep the fp32 partials below ~64 MiB
             const long long cap = (64LL << 20) / (g.w_elems * 4 > 0 ? g.w_elems * 4 : 1);
             if (want > cap) want = cap;
