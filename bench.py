@@ -25,6 +25,12 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 
+# HBM bytes per launch of the dominant kernel on the default workload (3x3 forward convolution of the 14x14 bottleneck,
+# N = 64), from the FETCH_SIZE / WRITE_SIZE passes summarised in profiles/bottleneck14_bf16_step_counters.md:
+# 8012 KiB x 2.000 (copy-kernel scale) fetched + 6272 KiB written.  Valid for the kernel those passes ran; set to None
+# whenever csrc/igemm_fast.hip or its launch heuristics change, until the passes are repeated.
+DOMINANT_KERNEL_TRAFFIC_BYTES = {("bottleneck14_bf16", 64): (8012 * 2.000 + 6272) * 1024}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -77,6 +83,16 @@ def cpu_baseline(wl_factory, images: int):
             grads[o.res] = g["dres"] if o.res not in grads else grads[o.res] + g["dres"]
     dt = time.perf_counter() - t0
     return wl.flops_step() / dt / 1e12, dt, orc.num_threads()
+
+
+def workloads_bytes(n, shp, b):
+    """Operands read once + result written once for one forward launch of block b (bf16)."""
+    c_in, h, w = shp[b.inp]
+    c_out, ho, wo = shp[b.out]
+    x = n * h * w * c_in * 2
+    y = n * ho * wo * c_out * 2
+    wgt = c_out * b.k * b.k * c_in * 2
+    return x + wgt + y + (y if b.res is not None else 0)
 
 
 def main():
@@ -165,7 +181,9 @@ def main():
                    "launch": "hip_graph" if args.launch == "graph" else "eager", "backward_lanes": lanes,
                    "flop_per_step": flops, "pct_mfma_peak": round(100 * value / MFMA_BF16_PEAK_TFLOPS, 2)},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "traffic": DOMINANT_KERNEL_TRAFFIC_BYTES.get((wl.name, n)), "traffic_unit": "bytes/launch",
+                     "algorithmic_bytes": workloads_bytes(n, shp, big),
                      "kernel": "igemm_fast_kernel", "launch": f"{big.name} forward", "avg_us": round(k_us, 3)},
     }
     if not args.no_cpu_baseline:
