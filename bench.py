@@ -37,7 +37,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", type=int, default=3, choices=[2, 3, 5])
+    ap.add_argument("--workload", type=int, default=3, choices=[2, 3, 4, 5])
     ap.add_argument("--batch", type=int, default=0, help="override N (0 = the workload's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--launch", choices=["eager", "graph"], default="eager",
@@ -109,9 +109,10 @@ def main():
     factories = {
         2: lambda n: workloads.stem_bf16(n=n),
         3: lambda n: workloads.bottleneck14_bf16(n=n),
+        4: lambda n: workloads.resnet50_infer_bf16(n=n),
         5: lambda n: workloads.stage2_train_bf16(n=n),
     }
-    default_n = {2: 32, 3: 64, 5: 128}[args.workload]
+    default_n = {2: 32, 3: 64, 4: 128, 5: 128}[args.workload]
     n = args.batch or default_n
     wl = factories[args.workload](n)
     torch.cuda.set_device(0)
@@ -151,7 +152,7 @@ def main():
 
     def launch():
         B.sol_block_fwd(seq.desc[big.layer], seq.act[big.inp], p["W"], p["scale"], p["shift"],
-                        seq.act[big.res] if big.res is not None else None, seq.act[big.out], None, 0, stream)
+                        seq.act[big.res] if big.res is not None else None, seq.act[big.out], seq.ws, None, stream)
 
     for _ in range(10):
         launch()

@@ -171,8 +171,34 @@ BwdPlan plan_bwd(const sol_block_desc* d, const Geometry& g) {
     return b;
 }
 
+// Forward workspace: only the few-input-channel kernel needs one (channel-padded image + packed weights).
+struct FwdPlan {
+    bool smallc;
+    size_t xp_off, wp_off, total;
+};
+FwdPlan plan_fwd(const sol_block_desc* d) {
+    FwdPlan f{};
+    f.smallc = d->dtype == SOL_BF16 && smallc_fwd_supported(d->C_in, d->C_out, d->KH, d->KW, d->stride) &&
+               env_int("SOL_SMALLC", 1) != 0;
+    if (f.smallc) {
+        f.xp_off = 0;
+        f.wp_off = align_up(smallc_padded_image_bytes(d->N, d->H, d->W));
+        f.total = f.wp_off + align_up(smallc_packed_weight_bytes(d->KH));
+    }
+    return f;
+}
+
 int fwd_bf16(const sol_block_desc* d, const Geometry& g, const void* x, const void* W, const float* scale,
-             const float* shift, const void* residual, void* y, hipStream_t stream) {
+             const float* shift, const void* residual, void* y, void* ws, hipStream_t stream) {
+    const FwdPlan plan = plan_fwd(d);
+    if (plan.smallc && !residual) {
+        unsigned char* wsb = (unsigned char*)ws;
+        SmallCParams sp{(const bf16_t*)x, (bf16_t*)(wsb + plan.xp_off), (const bf16_t*)W, (bf16_t*)(wsb + plan.wp_off),
+                        scale, shift, (bf16_t*)y, d->N, d->H, d->W, d->C_in, d->KH, d->KW, d->pad, g.Ho, g.Wo,
+                        (d->flags & SOL_RELU) ? 1 : 0};
+        if (launch_smallc_prepare(sp, stream) != hipSuccess) return SOL_ERR_LAUNCH;
+        return launch_smallc_fwd(sp, stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
+    }
     IgemmParams p{};
     p.src = (const bf16_t*)x;
     p.src_mask = nullptr;
@@ -292,24 +318,24 @@ SOL_API const char* sol_status_string(int status) {
 SOL_API size_t sol_block_workspace_bytes(const sol_block_desc* desc, int pass) {
     Geometry g;
     if (check_desc(desc, &g) != SOL_OK) return 0;
-    if (pass == SOL_PASS_FWD) return 0;
+    if (pass == SOL_PASS_FWD) return plan_fwd(desc).total;
     if (pass != SOL_PASS_BWD) return 0;
     return plan_bwd(desc, g).total;
 }
 
 SOL_API int sol_block_fwd(const sol_block_desc* desc, const void* x, const void* W, const float* scale, const float* shift,
                   const void* residual, void* y, void* ws, size_t ws_bytes, void* hip_stream) {
-    (void)ws;
-    (void)ws_bytes;
     Geometry g;
     if (int e = check_desc(desc, &g); e != SOL_OK) return e;
     if (!x || !W || !scale || !shift || !y) return SOL_ERR_NULL;
     if (misaligned(x) || misaligned(W) || misaligned(scale) || misaligned(shift) || misaligned(y) ||
-        misaligned(residual))
+        misaligned(residual) || misaligned(ws))
         return SOL_ERR_ALIGN;
+    const size_t need = plan_fwd(desc).total;
+    if (need > 0 && (!ws || ws_bytes < need)) return SOL_ERR_WORKSPACE;
     hipStream_t stream = (hipStream_t)hip_stream;
     clear_stale_error();
-    if (desc->dtype == SOL_BF16) return fwd_bf16(desc, g, x, W, scale, shift, residual, y, stream);
+    if (desc->dtype == SOL_BF16) return fwd_bf16(desc, g, x, W, scale, shift, residual, y, ws, stream);
     DirectParams p{};
     p.x = (const float*)x;
     p.W = (const float*)W;

@@ -144,12 +144,53 @@ hipError_t launch_l1_grad(int dtype, const void* y, const void* t, void* dy, lon
     return hipGetLastError();
 }
 
+// bf16, channels % 8 == 0: one thread per (output pixel, 8 channels), 16-byte loads and stores.  Comparing the
+// values as floats (bf16 << 16) keeps the result one of the inputs, so no rounding is involved.
+__global__ __launch_bounds__(256) void maxpool_bf16x8_kernel(const bf16_t* x, bf16_t* y, int N, int H, int W, int C, int k,
+                                                             int stride, int pad, int Ho, int Wo) {
+    const int c8 = C >> 3;
+    const long long total = (long long)N * Ho * Wo * c8;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int cc = (int)(idx % c8);
+    long long pix = idx / c8;
+    const int wo = (int)(pix % Wo);
+    pix /= Wo;
+    const int ho = (int)(pix % Ho);
+    const int n = (int)(pix / Ho);
+    float m[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) m[e] = -INFINITY;
+    for (int kh = 0; kh < k; ++kh) {
+        const int hi = ho * stride - pad + kh;
+        if ((unsigned)hi >= (unsigned)H) continue;
+        for (int kw = 0; kw < k; ++kw) {
+            const int wi = wo * stride - pad + kw;
+            if ((unsigned)wi >= (unsigned)W) continue;
+            const uintx4 v = *reinterpret_cast<const uintx4*>(x + (((long long)n * H + hi) * W + wi) * C + cc * 8);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float lo = __uint_as_float(v[e] << 16), hi2 = __uint_as_float(v[e] & 0xffff0000u);
+                m[2 * e] = lo > m[2 * e] ? lo : m[2 * e];
+                m[2 * e + 1] = hi2 > m[2 * e + 1] ? hi2 : m[2 * e + 1];
+            }
+        }
+    }
+    uintx4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = (__float_as_uint(m[2 * e]) >> 16) | (__float_as_uint(m[2 * e + 1]) & 0xffff0000u);
+    *reinterpret_cast<uintx4*>(y + idx * 8) = o;
+}
+
 hipError_t launch_maxpool(int dtype, const void* x, void* y, int N, int H, int W, int C, int k, int stride, int pad,
                           hipStream_t s) {
     const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
     const long long total = (long long)N * Ho * Wo * C;
     if (total <= 0) return hipSuccess;
-    if (dtype == 1)
+    if (dtype == 1 && (C & 7) == 0)
+        hipLaunchKernelGGL(maxpool_bf16x8_kernel, dim3(blocks_for(total >> 3)), dim3(256), 0, s, (const bf16_t*)x,
+                           (bf16_t*)y, N, H, W, C, k, stride, pad, Ho, Wo);
+    else if (dtype == 1)
         hipLaunchKernelGGL(maxpool_kernel<true>, dim3(blocks_for(total)), dim3(256), 0, s, x, y, N, H, W, C, k, stride,
                            pad, Ho, Wo);
     else

@@ -36,6 +36,22 @@ struct DirectParams {
 };
 
 
+struct SmallCParams {          // convolution with at most 4 input channels, 64 output channels, stride 2
+    const bf16_t* x;           // [N][H][W][C_in]
+    bf16_t* xp;                // workspace: [N][H][W][4], channel-padded copy of x
+    const bf16_t* Wt;          // [64][KH][KW][C_in]
+    bf16_t* wp;                // workspace: weights as MFMA operand image, [2*KH][64][2][8]
+    const float* scale;
+    const float* shift;
+    bf16_t* y;                 // [N][Ho][Wo][64]
+    int N, H, W, C_in, KH, KW, pad, Ho, Wo, relu;
+};
+bool smallc_fwd_supported(int C_in, int C_out, int KH, int KW, int stride);
+size_t smallc_padded_image_bytes(int N, int H, int W);
+size_t smallc_packed_weight_bytes(int KH);
+hipError_t launch_smallc_prepare(const SmallCParams& p, hipStream_t stream);
+hipError_t launch_smallc_fwd(const SmallCParams& p, hipStream_t stream);
+
 hipError_t launch_igemm(const IgemmParams& p, int tile, bool vec, bool mask, hipStream_t stream);
 void igemm_tile_shape(int tile, int* bp, int* bc);
 hipError_t launch_igemm_fast(const IgemmParams& p, int tile, int stages, hipStream_t stream);

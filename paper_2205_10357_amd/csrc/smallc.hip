@@ -1,0 +1,181 @@
+// Convolutions with very few input channels (the network stem: 7x7, stride 2, 3 -> 64 channels).
+//
+// With C_in = 3 a filter tap is 6 bytes of an NHWC row, so the implicit-GEMM kernels' 16-byte operand copies
+// do not apply and their element-wise fallback is two orders of magnitude off the memory roofline of this
+// layer (its output, not its arithmetic, is what must move).  Here:
+//
+//  * a preparation launch pads the image to 4 channels (8 bytes per pixel) and re-packs the weights into the
+//    exact register image of the MFMA weight operand;
+//  * K is ordered (kh, kw', ci) with kw' = 0..7 and ci = 0..3: one filter row is a "run" of 8 consecutive
+//    padded pixels = 32 K elements = two 16-deep MFMA steps, K = 32 * KH (taps kw' >= KW and channel 3 carry
+//    zero weights);
+//  * a workgroup computes 128 consecutive output pixels of one output row for all 64 output channels.  It
+//    stages the KH raw image rows it needs (128 * stride + 8 pixels each) in LDS; the MFMA pixel operand of
+//    lane (pixel p, half h) at step (kh, half-run r) is the 16 bytes at pixel p*stride + 4r + 2h of row kh --
+//    a plain aligned ds_read_b128 for stride 2, consecutive lanes 16 bytes apart: no im2col copy exists anywhere;
+//  * all weight fragments of a wave (2 x 2*KH x 16 bytes per lane) stay in registers across the tiles a
+//    workgroup processes;
+//  * the accumulators hold 4 consecutive output channels per register group, so the epilogue (affine, ReLU,
+//    one rounding) stores 8-byte pieces of NHWC rows directly.
+#include "launch.h"
+
+namespace sol {
+
+constexpr int SC_CO = 64;          // output channels (two 32-row MFMA tiles)
+constexpr int SC_TILE = 128;       // output pixels of one row per workgroup tile
+constexpr int SC_MAXKH = 8;
+
+// ---- preparation: image -> 4 channels, weights -> operand image --------------------------------------
+// Workgroups [0, pad_blocks) pad pixels (one thread per pixel), the rest pack weights: element
+// (step ks, channel co, half h, e) = W[co][kh = ks/2][kw' = 4*(ks&1) + 2*h + e/4][ci = e%4] or 0.
+__global__ __launch_bounds__(256) void smallc_prepare_kernel(const SmallCParams p) {
+    const long long pixels = (long long)p.N * p.H * p.W;
+    const int pad_blocks = (int)((pixels + 255) / 256);
+    if ((int)blockIdx.x < pad_blocks) {
+        const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+        if (i >= pixels) return;
+        const bf16_t* src = p.x + i * p.C_in;
+        uintx2 v = {0u, 0u};
+        v[0] = (uint32_t)src[0] | (p.C_in > 1 ? (uint32_t)src[1] << 16 : 0u);
+        if (p.C_in > 2) v[1] = (uint32_t)src[2] | (p.C_in > 3 ? (uint32_t)src[3] << 16 : 0u);
+        *reinterpret_cast<uintx2*>(p.xp + i * 4) = v;
+    } else {
+        const int i = ((int)blockIdx.x - pad_blocks) * 256 + threadIdx.x;     // one 16-byte fragment piece per thread
+        const int total = 2 * p.KH * SC_CO * 2;
+        if (i >= total) return;
+        const int h = i & 1, co = (i >> 1) % SC_CO, ks = (i >> 1) / SC_CO;
+        const int kh = ks >> 1;
+        unsigned short e[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int kw = 4 * (ks & 1) + 2 * h + (j >> 2), ci = j & 3;
+            e[j] = (kw < p.KW && ci < p.C_in) ? p.Wt[(((long long)co * p.KH + kh) * p.KW + kw) * p.C_in + ci] : (unsigned short)0;
+        }
+        uintx4 v = {(uint32_t)e[0] | ((uint32_t)e[1] << 16), (uint32_t)e[2] | ((uint32_t)e[3] << 16),
+                    (uint32_t)e[4] | ((uint32_t)e[5] << 16), (uint32_t)e[6] | ((uint32_t)e[7] << 16)};
+        reinterpret_cast<uintx4*>(p.wp)[i] = v;
+    }
+}
+
+// ---- forward ---------------------------------------------------------------------------------------------
+template <int KH>
+__global__ __launch_bounds__(256) void smallc_fwd_kernel(const SmallCParams p) {
+    constexpr int KS = 2 * KH;                       // 16-deep MFMA steps
+    constexpr int PW = SC_TILE * 2 + 8;              // staged pixels per image row (stride 2)
+    __shared__ __align__(16) uintx2 patch[KH * PW];  // [kh][pixel] 8 bytes each
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int segs = (p.Wo + SC_TILE - 1) / SC_TILE;
+    const int tiles = p.N * p.Ho * segs;
+
+    // weight fragments: lane (row co = 32*i + lane%32, half lane/32) of every step, 16 bytes each
+    uintx4 wf[2][KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            wf[i][ks] = reinterpret_cast<const uintx4*>(p.wp)[(ks * SC_CO + 32 * i + (lane & 31)) * 2 + (lane >> 5)];
+    // affine parameters of this lane's accumulator rows: co = 32*i + 8*g + 4*(lane/32) + e
+    floatx4 sc[2][4], sh[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int co = 32 * i + 8 * g + 4 * (lane >> 5);
+            sc[i][g] = *reinterpret_cast<const floatx4*>(p.scale + co);
+            sh[i][g] = *reinterpret_cast<const floatx4*>(p.shift + co);
+        }
+
+    for (int t = blockIdx.x; t < tiles; t += gridDim.x) {
+        const int seg = t % segs, row = t / segs;
+        const int ho = row % p.Ho, n = row / p.Ho;
+        const int wo0 = seg * SC_TILE;
+        const int wi0 = wo0 * 2 - p.pad;             // image column of staged pixel 0
+        __syncthreads();                             // the previous tile's fragments have been read
+#pragma unroll
+        for (int kh = 0; kh < KH; ++kh) {
+            const int hi = ho * 2 - p.pad + kh;
+            const bool row_ok = (unsigned)hi < (unsigned)p.H;
+            const bf16_t* src = p.xp + (((long long)n * p.H + hi) * p.W) * 4;
+            for (int q = tid; q < PW; q += 256) {
+                const int wi = wi0 + q;
+                uintx2 v = {0u, 0u};
+                if (row_ok && (unsigned)wi < (unsigned)p.W) v = *reinterpret_cast<const uintx2*>(src + (long long)wi * 4);
+                patch[kh * PW + q] = v;
+            }
+        }
+        __syncthreads();
+
+        floatx16 acc[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+        const int pl = wave * 32 + (lane & 31);      // output pixel of this lane inside the tile
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int q = pl * 2 + 4 * (ks & 1) + 2 * (lane >> 5);
+            const bf16x8 pf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(&patch[(ks >> 1) * PW + q]));
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf[i][ks]), pf, acc[i], 0, 0, 0);
+        }
+
+        const int wo = wo0 + pl;
+        if (wo < p.Wo) {
+            bf16_t* dst = p.y + (((long long)n * p.Ho + ho) * p.Wo + wo) * SC_CO + 4 * (lane >> 5);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        v[e] = fmaf(sc[i][g][e], acc[i][4 * g + e], sh[i][g][e]);
+                        if (p.relu) v[e] = v[e] > 0.f ? v[e] : 0.f;
+                    }
+                    *reinterpret_cast<uintx2*>(dst + 32 * i + 8 * g) = uintx2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+                }
+        }
+    }
+}
+
+bool smallc_fwd_supported(int C_in, int C_out, int KH, int KW, int stride) {
+    return C_in >= 1 && C_in <= 4 && C_out == SC_CO && KH >= 1 && KH <= SC_MAXKH && KW >= 1 && KW <= 8 && stride == 2;
+}
+
+size_t smallc_padded_image_bytes(int N, int H, int W) { return (size_t)N * H * W * 4 * 2; }
+size_t smallc_packed_weight_bytes(int KH) { return (size_t)2 * KH * SC_CO * 2 * 16; }
+
+hipError_t launch_smallc_prepare(const SmallCParams& p, hipStream_t stream) {
+    const long long pixels = (long long)p.N * p.H * p.W;
+    const int pad_blocks = (int)((pixels + 255) / 256);
+    const int pack_blocks = (2 * p.KH * SC_CO * 2 + 255) / 256;
+    hipLaunchKernelGGL(smallc_prepare_kernel, dim3(pad_blocks + pack_blocks), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+template <int KH>
+static hipError_t launch_smallc_fwd_kh(const SmallCParams& p, hipStream_t stream) {
+    const int segs = (p.Wo + SC_TILE - 1) / SC_TILE;
+    const long long tiles = (long long)p.N * p.Ho * segs;
+    const int grid = (int)(tiles < 1024 ? tiles : 1024);       // several tiles per workgroup amortise the weight fetch
+    hipLaunchKernelGGL(smallc_fwd_kernel<KH>, dim3(grid), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_smallc_fwd(const SmallCParams& p, hipStream_t stream) {
+    switch (p.KH) {
+        case 1: return launch_smallc_fwd_kh<1>(p, stream);
+        case 2: return launch_smallc_fwd_kh<2>(p, stream);
+        case 3: return launch_smallc_fwd_kh<3>(p, stream);
+        case 4: return launch_smallc_fwd_kh<4>(p, stream);
+        case 5: return launch_smallc_fwd_kh<5>(p, stream);
+        case 6: return launch_smallc_fwd_kh<6>(p, stream);
+        case 7: return launch_smallc_fwd_kh<7>(p, stream);
+        case 8: return launch_smallc_fwd_kh<8>(p, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace sol

@@ -93,6 +93,7 @@ class Sequencer:
             d = B.BlockDesc(n, h, w, o.c_in, o.c_out, o.k, o.k, o.stride, o.pad, self.sol_dtype,
                             B.SOL_RELU if o.relu else 0)
             self.desc[o.layer] = d
+            ws_bytes = max(ws_bytes, B.sol_block_workspace_bytes(d, B.SOL_PASS_FWD))
             if wl.train:
                 ws_bytes = max(ws_bytes, B.sol_block_workspace_bytes(d, B.SOL_PASS_BWD),
                                B.sol_block_workspace_bytes(
@@ -128,7 +129,7 @@ class Sequencer:
                 p = self.params[o.layer]
                 B.sol_block_fwd(self.desc[o.layer], self.act[o.inp], p["W"], p["scale"], p["shift"],
                                 self.act[o.res] if o.res is not None else None, self.act[o.out],
-                                None, 0, stream)
+                                self.ws, None, stream)
             else:
                 c, h, w = self.shapes[o.inp]
                 B.sol_maxpool_fwd(self.sol_dtype, self.act[o.inp], self.act[o.out], self.wl.n, h, w, c,

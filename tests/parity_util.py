@@ -89,7 +89,9 @@ def gpu_block(case, need_dx=True, want_dres=False, addend=None, addend_mask=None
     am = to_dev(addend_mask, bf16) if addend_mask is not None else None
     dxm = to_dev(dx_mask, bf16) if dx_mask is not None else None
 
-    B.sol_block_fwd(desc, x, w, scale, shift, res, y, None, 0)
+    fws_bytes = B.sol_block_workspace_bytes(desc, B.SOL_PASS_FWD)
+    fws = torch.full((fws_bytes // 4 + 64,), float("nan"), dtype=torch.float32, device="cuda") if fws_bytes else None
+    B.sol_block_fwd(desc, x, w, scale, shift, res, y, fws, fws_bytes)
     B.sol_l1_loss_grad(dt, y, t, dy, y.numel(), premasked and d.relu)
     if premasked:           # gradient already masked by this block's ReLU: backward without flag and y
         desc = B.BlockDesc(d.N, d.H, d.W, d.C_in, d.C_out, d.KH, d.KW, d.stride, d.pad, dt,

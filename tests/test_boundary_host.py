@@ -85,6 +85,12 @@ def test_pointer_validation():
 
 def test_workspace_sizes():
     assert B.sol_block_workspace_bytes(desc(), B.SOL_PASS_FWD) == 0
+    # few input channels (the stem): forward needs the channel-padded image and the packed weights
+    stem = desc(N=2, H=32, W=32, C_in=3, C_out=64, KH=7, KW=7, stride=2, pad=3)
+    need = B.sol_block_workspace_bytes(stem, B.SOL_PASS_FWD)
+    assert need >= 2 * 32 * 32 * 4 * 2 + 14 * 64 * 32
+    assert B.sol_block_fwd(stem, FAKE, FAKE, FAKE, FAKE, None, FAKE, None, 0, stream=0, check=False) == -5
+    assert B.sol_block_fwd(stem, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, need - 1, stream=0, check=False) == -5
     d = desc(N=64, H=14, W=14, C_in=256, C_out=256)
     need = B.sol_block_workspace_bytes(d, B.SOL_PASS_BWD)
     k = 9 * 256

@@ -89,6 +89,9 @@ def test_bf16_resnet50_layer_shapes(spec):
     dict(N=2, H=7, W=9, C_in=16, C_out=40, K=1, stride=2, pad=0, relu=False), # 1x1/s2: 3 of 4 pixel classes see no tap
     dict(N=2, H=14, W=14, C_in=64, C_out=512, K=1, stride=2, pad=0, relu=False),  # same, long reduction (deep copy ring)
     dict(N=1, H=12, W=12, C_in=3, C_out=8, K=7, stride=2, pad=3),             # stem-like with a data gradient
+    dict(N=2, H=30, W=530, C_in=3, C_out=64, K=7, stride=2, pad=3),           # few-channel kernel: 3 row segments, ragged
+    dict(N=3, H=9, W=11, C_in=4, C_out=64, K=3, stride=2, pad=1, relu=False), # few-channel kernel, 3x3, 4 channels
+    dict(N=1, H=16, W=16, C_in=1, C_out=64, K=5, stride=2, pad=2),            # few-channel kernel, 1 channel
     dict(N=1, H=33, W=31, C_in=64, C_out=136, K=3, stride=1, pad=1),          # ragged in pixels and channels
     dict(N=2, H=6, W=6, C_in=8, C_out=8, K=5, stride=1, pad=2),               # 5x5
     dict(N=1, H=8, W=8, C_in=16, C_out=16, K=3, stride=1, pad=0),             # no padding
