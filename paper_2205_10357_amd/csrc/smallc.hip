@@ -13,10 +13,12 @@
 //    stages the KH raw image rows it needs (128 * stride + 8 pixels each) in LDS; the MFMA pixel operand of
 //    lane (pixel p, half h) at step (kh, half-run r) is the 16 bytes at pixel p*stride + 4r + 2h of row kh --
 //    a plain aligned ds_read_b128 for stride 2, consecutive lanes 16 bytes apart: no im2col copy exists anywhere;
-//  * all weight fragments of a wave (2 x 2*KH x 16 bytes per lane) stay in registers across the tiles a
-//    workgroup processes;
+//  * all weight fragments of a wave (its 32 channels: 2*KH x 16 bytes per lane) stay in registers across the
+//    tiles a workgroup processes;
 //  * the accumulators hold 4 consecutive output channels per register group, so the epilogue (affine, ReLU,
 //    one rounding) stores 8-byte pieces of NHWC rows directly.
+#include <stdlib.h>
+
 #include "launch.h"
 
 namespace sol {
@@ -25,20 +27,33 @@ constexpr int SC_CO = 64;          // output channels (two 32-row MFMA tiles)
 constexpr int SC_TILE = 128;       // output pixels of one row per workgroup tile
 constexpr int SC_MAXKH = 8;
 
+static inline __host__ __device__ int smallc_pad_blocks(long long pixels) { return (int)((pixels + 1023) / 1024); }
+
 // ---- preparation: image -> 4 channels, weights -> operand image --------------------------------------
-// Workgroups [0, pad_blocks) pad pixels (one thread per pixel), the rest pack weights: element
+// Workgroups [0, pad_blocks) pad pixels (four per thread), the rest pack weights: element
 // (step ks, channel co, half h, e) = W[co][kh = ks/2][kw' = 4*(ks&1) + 2*h + e/4][ci = e%4] or 0.
 __global__ __launch_bounds__(256) void smallc_prepare_kernel(const SmallCParams p) {
     const long long pixels = (long long)p.N * p.H * p.W;
-    const int pad_blocks = (int)((pixels + 255) / 256);
+    const int pad_blocks = smallc_pad_blocks(pixels);
     if ((int)blockIdx.x < pad_blocks) {
-        const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-        if (i >= pixels) return;
-        const bf16_t* src = p.x + i * p.C_in;
-        uintx2 v = {0u, 0u};
-        v[0] = (uint32_t)src[0] | (p.C_in > 1 ? (uint32_t)src[1] << 16 : 0u);
-        if (p.C_in > 2) v[1] = (uint32_t)src[2] | (p.C_in > 3 ? (uint32_t)src[3] << 16 : 0u);
-        *reinterpret_cast<uintx2*>(p.xp + i * 4) = v;
+        // four pixels per thread; with 3 channels they are 24 contiguous bytes (8-byte aligned) -> 32 bytes out
+        const long long i4 = ((long long)blockIdx.x * 256 + threadIdx.x) * 4;
+        if (i4 >= pixels) return;
+        if (p.C_in == 3 && i4 + 4 <= pixels) {
+            const uintx2* src = reinterpret_cast<const uintx2*>(p.x + i4 * 3);
+            const uintx2 a = src[0], b = src[1], c = src[2];      // c0 c1 | c2 d0 | d1 d2 | e0 e1 | e2 f0 | f1 f2
+            uintx4* dst = reinterpret_cast<uintx4*>(p.xp + i4 * 4);
+            dst[0] = uintx4{a[0], a[1] & 0xffffu, (a[1] >> 16) | (b[0] << 16), b[0] >> 16};
+            dst[1] = uintx4{b[1], c[0] & 0xffffu, (c[0] >> 16) | (c[1] << 16), c[1] >> 16};
+            return;
+        }
+        for (long long i = i4; i < i4 + 4 && i < pixels; ++i) {
+            const bf16_t* src = p.x + i * p.C_in;
+            uintx2 v = {0u, 0u};
+            v[0] = (uint32_t)src[0] | (p.C_in > 1 ? (uint32_t)src[1] << 16 : 0u);
+            if (p.C_in > 2) v[1] = (uint32_t)src[2] | (p.C_in > 3 ? (uint32_t)src[3] << 16 : 0u);
+            *reinterpret_cast<uintx2*>(p.xp + i * 4) = v;
+        }
     } else {
         const int i = ((int)blockIdx.x - pad_blocks) * 256 + threadIdx.x;     // one 16-byte fragment piece per thread
         const int total = 2 * p.KH * SC_CO * 2;
@@ -59,83 +74,113 @@ __global__ __launch_bounds__(256) void smallc_prepare_kernel(const SmallCParams 
 
 // ---- forward ---------------------------------------------------------------------------------------------
 template <int KH>
-__global__ __launch_bounds__(256) void smallc_fwd_kernel(const SmallCParams p) {
+__global__ __launch_bounds__(256, 2) void smallc_fwd_kernel(const SmallCParams p) {
     constexpr int KS = 2 * KH;                       // 16-deep MFMA steps
     constexpr int PW = SC_TILE * 2 + 8;              // staged pixels per image row (stride 2)
+    constexpr int OP = 17;                           // 8-byte pieces per staged output pixel (16 + 1 of padding)
     __shared__ __align__(16) uintx2 patch[KH * PW];  // [kh][pixel] 8 bytes each
+    __shared__ __align__(16) uintx2 outs[SC_TILE * OP];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int segs = (p.Wo + SC_TILE - 1) / SC_TILE;
     const int tiles = p.N * p.Ho * segs;
 
-    // weight fragments: lane (row co = 32*i + lane%32, half lane/32) of every step, 16 bytes each
-    uintx4 wf[2][KS];
+    // wave grid 2 (pixel halves of 64) x 2 (channel halves of 32): every wave keeps the weight fragments of its
+    // 32 channels for all steps in registers -- lane (row co = 32*wc + lane%32, half lane/32), 16 bytes per step
+    const int wp = wave & 1, wc = wave >> 1;
+    uintx4 wf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
+        wf[ks] = reinterpret_cast<const uintx4*>(p.wp)[(ks * SC_CO + 32 * wc + (lane & 31)) * 2 + (lane >> 5)];
+    // affine parameters of this lane's accumulator rows: co = 32*wc + 8*g + 4*(lane/32) + e
+    floatx4 sc[4], sh[4];
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-            wf[i][ks] = reinterpret_cast<const uintx4*>(p.wp)[(ks * SC_CO + 32 * i + (lane & 31)) * 2 + (lane >> 5)];
-    // affine parameters of this lane's accumulator rows: co = 32*i + 8*g + 4*(lane/32) + e
-    floatx4 sc[2][4], sh[2][4];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int co = 32 * i + 8 * g + 4 * (lane >> 5);
-            sc[i][g] = *reinterpret_cast<const floatx4*>(p.scale + co);
-            sh[i][g] = *reinterpret_cast<const floatx4*>(p.shift + co);
-        }
+    for (int g = 0; g < 4; ++g) {
+        const int co = 32 * wc + 8 * g + 4 * (lane >> 5);
+        sc[g] = *reinterpret_cast<const floatx4*>(p.scale + co);
+        sh[g] = *reinterpret_cast<const floatx4*>(p.shift + co);
+    }
 
-    for (int t = blockIdx.x; t < tiles; t += gridDim.x) {
+    // the staged rows of a tile, fetched by this thread: flat element e = tid + 256*j of [KH][PW]
+    constexpr int NL = (KH * PW + 255) / 256;
+    auto fetch = [&](int t, uintx2 (&v)[NL]) {
+        const int seg = t % segs, row = t / segs;
+        const int ho = row % p.Ho, n = row / p.Ho;
+        const int wi0 = seg * SC_TILE * 2 - p.pad;   // image column of staged pixel 0
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            const int e = tid + 256 * j;
+            const int kh = e / PW, q = e - kh * PW;
+            const int hi = ho * 2 - p.pad + kh, wi = wi0 + q;
+            v[j] = uintx2{0u, 0u};
+            if (e < KH * PW && (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W)
+                v[j] = *reinterpret_cast<const uintx2*>(p.xp + (((long long)n * p.H + hi) * p.W + wi) * 4);
+        }
+    };
+    auto stage = [&](const uintx2 (&v)[NL]) {
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            const int e = tid + 256 * j;
+            if (e < KH * PW) patch[e] = v[j];
+        }
+    };
+
+    uintx2 nextv[NL];
+    int t = blockIdx.x;
+    if (t < tiles) fetch(t, nextv);
+    for (; t < tiles; t += gridDim.x) {
         const int seg = t % segs, row = t / segs;
         const int ho = row % p.Ho, n = row / p.Ho;
         const int wo0 = seg * SC_TILE;
-        const int wi0 = wo0 * 2 - p.pad;             // image column of staged pixel 0
         __syncthreads();                             // the previous tile's fragments have been read
-#pragma unroll
-        for (int kh = 0; kh < KH; ++kh) {
-            const int hi = ho * 2 - p.pad + kh;
-            const bool row_ok = (unsigned)hi < (unsigned)p.H;
-            const bf16_t* src = p.xp + (((long long)n * p.H + hi) * p.W) * 4;
-            for (int q = tid; q < PW; q += 256) {
-                const int wi = wi0 + q;
-                uintx2 v = {0u, 0u};
-                if (row_ok && (unsigned)wi < (unsigned)p.W) v = *reinterpret_cast<const uintx2*>(src + (long long)wi * 4);
-                patch[kh * PW + q] = v;
-            }
-        }
+        stage(nextv);
         __syncthreads();
+        if (t + (int)gridDim.x < tiles) fetch(t + gridDim.x, nextv);      // in flight during this tile's arithmetic
 
-        floatx16 acc[2];
+        floatx16 acc[2];                             // pixel tiles j = 0, 1 of this wave's half
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
-        const int pl = wave * 32 + (lane & 31);      // output pixel of this lane inside the tile
+            for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+        const int pl0 = wp * 64 + (lane & 31);       // output pixel of this lane inside the tile (tile j adds 32)
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            const int q = pl * 2 + 4 * (ks & 1) + 2 * (lane >> 5);
-            const bf16x8 pf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(&patch[(ks >> 1) * PW + q]));
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf[i][ks]), pf, acc[i], 0, 0, 0);
+            const int q = pl0 * 2 + 4 * (ks & 1) + 2 * (lane >> 5);
+            const uintx2* rowp = &patch[(ks >> 1) * PW + q];
+            const bf16x8 pf0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(rowp));
+            const bf16x8 pf1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(rowp + 64));
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf[ks]), pf0, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf[ks]), pf1, acc[1], 0, 0, 0);
         }
 
-        const int wo = wo0 + pl;
-        if (wo < p.Wo) {
-            bf16_t* dst = p.y + (((long long)n * p.Ho + ho) * p.Wo + wo) * SC_CO + 4 * (lane >> 5);
+        // epilogue: affine, ReLU and the one rounding in the accumulator layout (4 consecutive channels per
+        // register group), then through LDS so that every store instruction writes whole 128-byte pixel rows
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    float v[4];
+            for (int g = 0; g < 4; ++g) {
+                float v[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        v[e] = fmaf(sc[i][g][e], acc[i][4 * g + e], sh[i][g][e]);
-                        if (p.relu) v[e] = v[e] > 0.f ? v[e] : 0.f;
-                    }
-                    *reinterpret_cast<uintx2*>(dst + 32 * i + 8 * g) = uintx2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+                for (int e = 0; e < 4; ++e) {
+                    v[e] = fmaf(sc[g][e], acc[j][4 * g + e], sh[g][e]);
+                    if (p.relu) v[e] = v[e] > 0.f ? v[e] : 0.f;
                 }
+                outs[(pl0 + 32 * j) * OP + 8 * wc + 2 * g + (lane >> 5)] =
+                    uintx2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+            }
+        __syncthreads();
+        {
+            bf16_t* dst = p.y + (((long long)n * p.Ho + ho) * p.Wo + wo0) * SC_CO;
+            const int valid = p.Wo - wo0 < SC_TILE ? p.Wo - wo0 : SC_TILE;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int e = tid + 256 * j;               // 16-byte piece e of the tile's [128][64] bf16 rows
+                const int px = e >> 3, c = e & 7;
+                if (px < valid) {
+                    const uintx2 a = outs[px * OP + 2 * c], b = outs[px * OP + 2 * c + 1];
+                    *reinterpret_cast<uintx4*>(dst + px * SC_CO + c * 8) = uintx4{a[0], a[1], b[0], b[1]};
+                }
+            }
         }
     }
 }
@@ -149,7 +194,7 @@ size_t smallc_packed_weight_bytes(int KH) { return (size_t)2 * KH * SC_CO * 2 * 
 
 hipError_t launch_smallc_prepare(const SmallCParams& p, hipStream_t stream) {
     const long long pixels = (long long)p.N * p.H * p.W;
-    const int pad_blocks = (int)((pixels + 255) / 256);
+    const int pad_blocks = smallc_pad_blocks(pixels);
     const int pack_blocks = (2 * p.KH * SC_CO * 2 + 255) / 256;
     hipLaunchKernelGGL(smallc_prepare_kernel, dim3(pad_blocks + pack_blocks), dim3(256), 0, stream, p);
     return hipGetLastError();
@@ -159,7 +204,9 @@ template <int KH>
 static hipError_t launch_smallc_fwd_kh(const SmallCParams& p, hipStream_t stream) {
     const int segs = (p.Wo + SC_TILE - 1) / SC_TILE;
     const long long tiles = (long long)p.N * p.Ho * segs;
-    const int grid = (int)(tiles < 1024 ? tiles : 1024);       // several tiles per workgroup amortise the weight fetch
+    const char* gv = getenv("SOL_SMALLC_GRID");
+    const long long cap = gv && *gv ? atoi(gv) : 512;          // two workgroups per compute unit
+    const int grid = (int)(tiles < cap ? tiles : cap);         // several tiles per workgroup amortise the weight fetch
     hipLaunchKernelGGL(smallc_fwd_kernel<KH>, dim3(grid), dim3(256), 0, stream, p);
     return hipGetLastError();
 }
