@@ -135,6 +135,10 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, hipStream_t stre
 struct BwdPlan {
     int splits, m_per_split, tiles_k, tiles_c;
     size_t wpack_off, part_off, dshift_off, total;
+    // few-input-channel layers: channel-padded image and per-workgroup partials of their own weight-gradient kernel
+    bool smallc;
+    int sc_parts;
+    size_t sc_xp_off, sc_part_off;
 };
 
 BwdPlan plan_bwd(const sol_block_desc* d, const Geometry& g) {
@@ -168,6 +172,14 @@ BwdPlan plan_bwd(const sol_block_desc* d, const Geometry& g) {
     }
     b.dshift_off = b.part_off + align_up((size_t)b.splits * g.w_elems * 4);
     b.total = b.dshift_off + align_up((size_t)b.splits * d->C_out * 4);
+    b.smallc = d->dtype == SOL_BF16 && smallc_fwd_supported(d->C_in, d->C_out, d->KH, d->KW, d->stride) &&
+               env_int("SOL_SMALLC", 1) != 0;
+    if (b.smallc) {
+        b.sc_parts = smallc_wgrad_parts(d->N, g.Ho, g.Wo);
+        b.sc_xp_off = b.total;
+        b.sc_part_off = b.sc_xp_off + align_up(smallc_padded_image_bytes(d->N, d->H, d->W));
+        b.total = b.sc_part_off + align_up(smallc_wgrad_partial_bytes(b.sc_parts));
+    }
     return b;
 }
 
@@ -416,6 +428,16 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
 
     // ---- weight branch: split weight-gradient GEMM, then the reduction that also finishes dscale, dshift ----
     auto weight_branch = [&](hipStream_t st) -> int {
+        if (plan.smallc && !relu) {      // few input channels, gradient already masked: kernels of their own
+            bf16_t* xp = (bf16_t*)(wsb + plan.sc_xp_off);
+            SmallCParams pp{(const bf16_t*)x, xp, (const bf16_t*)W, nullptr, scale, nullptr, nullptr, desc->N, desc->H,
+                            desc->W, desc->C_in, desc->KH, desc->KW, desc->pad, g.Ho, g.Wo, 0};
+            if (launch_smallc_prepare(pp, st) != hipSuccess) return SOL_ERR_LAUNCH;
+            SmallCWgradParams wp{(const bf16_t*)dy, xp, (const bf16_t*)W, scale, (float*)(wsb + plan.sc_part_off), dW,
+                                 dscale, dshift, desc->N, desc->H, desc->W, desc->C_in, desc->KH, desc->KW, desc->pad,
+                                 g.Ho, g.Wo, plan.sc_parts, (desc->flags & SOL_DW_ACCUMULATE) ? 1 : 0};
+            return launch_smallc_wgrad(wp, st) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
+        }
         if (desc->dtype == SOL_BF16) {
             WgradParams wp{};
             wp.dy = (const bf16_t*)dy;

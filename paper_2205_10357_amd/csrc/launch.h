@@ -46,6 +46,20 @@ struct SmallCParams {          // convolution with at most 4 input channels, 64 
     bf16_t* y;                 // [N][Ho][Wo][64]
     int N, H, W, C_in, KH, KW, pad, Ho, Wo, relu;
 };
+struct SmallCWgradParams {     // weight gradient of the same layers (dy already masked)
+    const bf16_t* dy;          // [N][Ho][Wo][64]
+    const bf16_t* xp;          // channel-padded image (smallc_prepare)
+    const bf16_t* Wt;          // for dscale
+    const float* scale;
+    float* partial;            // workspace: [nparts][64][264] fp32
+    float* dW;                 // [64][KH][KW][C_in]
+    float* dscale;
+    float* dshift;
+    int N, H, W, C_in, KH, KW, pad, Ho, Wo, nparts, accumulate;
+};
+int smallc_wgrad_parts(int N, int Ho, int Wo);
+size_t smallc_wgrad_partial_bytes(int nparts);
+hipError_t launch_smallc_wgrad(const SmallCWgradParams& p, hipStream_t stream);
 bool smallc_fwd_supported(int C_in, int C_out, int KH, int KW, int stride);
 size_t smallc_padded_image_bytes(int N, int H, int W);
 size_t smallc_packed_weight_bytes(int KH);

@@ -26,6 +26,7 @@ namespace sol {
 constexpr int SC_CO = 64;          // output channels (two 32-row MFMA tiles)
 constexpr int SC_TILE = 128;       // output pixels of one row per workgroup tile
 constexpr int SC_MAXKH = 8;
+constexpr int SC_PK = 264;         // floats per channel row of a weight-gradient partial (256 columns + dshift + padding)
 
 static inline __host__ __device__ int smallc_pad_blocks(long long pixels) { return (int)((pixels + 1023) / 1024); }
 
@@ -195,7 +196,7 @@ size_t smallc_packed_weight_bytes(int KH) { return (size_t)2 * KH * SC_CO * 2 * 
 hipError_t launch_smallc_prepare(const SmallCParams& p, hipStream_t stream) {
     const long long pixels = (long long)p.N * p.H * p.W;
     const int pad_blocks = smallc_pad_blocks(pixels);
-    const int pack_blocks = (2 * p.KH * SC_CO * 2 + 255) / 256;
+    const int pack_blocks = p.wp ? (2 * p.KH * SC_CO * 2 + 255) / 256 : 0;     // no packed weights wanted: pad only
     hipLaunchKernelGGL(smallc_prepare_kernel, dim3(pad_blocks + pack_blocks), dim3(256), 0, stream, p);
     return hipGetLastError();
 }
@@ -221,6 +222,189 @@ hipError_t launch_smallc_fwd(const SmallCParams& p, hipStream_t stream) {
         case 6: return launch_smallc_fwd_kh<6>(p, stream);
         case 7: return launch_smallc_fwd_kh<7>(p, stream);
         case 8: return launch_smallc_fwd_kh<8>(p, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// ---- weight gradient ------------------------------------------------------------------------------------
+// G[k'][co] = sum over pixels of P[px][k'] * g[px][co], with P the same (kh, kw', ci) view of the staged image
+// rows as in the forward kernel: for filter row kh, P[px][0..31] are the 64 bytes at pixel 2*px of staged row kh
+// (rows of this "matrix" are 16 bytes apart and overlap).  The reduction index is the pixel, which is the row
+// index of both operands in memory, so both MFMA operands come from transposing LDS reads (ds_read_b64_tr_b16:
+// per 16 lanes a 4 x 16 block, 4 reduction rows x 16 columns).  A workgroup keeps its accumulators over all the
+// row segments it processes and writes one fp32 partial [64 co][264] (32*KH gradient columns, column 256 = the
+// column sum of g, i.e. dshift) at the end; smallc_wgrad_reduce_kernel adds the workgroups in a fixed order.
+// Waves: channel tile (wave & 1) x filter rows {kh : kh % 2 == wave / 2}; the odd-row waves also own dshift.
+template <int KH>
+__global__ __launch_bounds__(256) void smallc_wgrad_kernel(const SmallCWgradParams p) {
+    constexpr int PW = SC_TILE * 2 + 8;
+    constexpr int GP = 160;                          // bytes per staged gradient row (128 + 32: the 4 rows of a
+                                                     // transposing read fall into different banks)
+    constexpr int NU = 4;                            // filter rows per wave (kh = khs + 2*u)
+    __shared__ __align__(16) uintx2 patch[KH * PW];
+    __shared__ __align__(16) unsigned char gt[SC_TILE * GP];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // wave-uniform: the filter-row tests below are scalar
+    const int cot = wave & 1, khs = wave >> 1;
+    const int grp = lane >> 4, j = lane & 15;
+    const int segs = (p.Wo + SC_TILE - 1) / SC_TILE;
+    const int tiles = p.N * p.Ho * segs;
+
+    floatx16 acc[NU], accs;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+#pragma unroll
+        for (int u = 0; u < NU; ++u) acc[u][v] = 0.f;
+        accs[v] = 0.f;
+    }
+    bf16x8 ones;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
+
+    // lane part of the transposing-read addresses (reduction row 8*(grp>>1) + (j>>2), column piece 16*(grp&1) + 4*(j&3))
+    const int mrow = 8 * (grp >> 1) + (j >> 2);
+    const unsigned char* gbase = gt + mrow * GP + (32 * cot + 16 * (grp & 1) + 4 * (j & 3)) * 2;
+    const unsigned char* pbase = reinterpret_cast<const unsigned char*>(patch) + mrow * 16 + 32 * (grp & 1) + 8 * (j & 3);
+
+    for (int t = blockIdx.x; t < tiles; t += gridDim.x) {
+        const int seg = t % segs, row = t / segs;
+        const int ho = row % p.Ho, n = row / p.Ho;
+        const int wo0 = seg * SC_TILE;
+        const int wi0 = wo0 * 2 - p.pad;
+        const int valid = p.Wo - wo0 < SC_TILE ? p.Wo - wo0 : SC_TILE;
+        __syncthreads();                             // the previous tile has been read
+        // gradient rows: 128 pixels x 64 channels, 16-byte pieces; rows past the end of the image row are zero
+        const bf16_t* gsrc = p.dy + (((long long)n * p.Ho + ho) * p.Wo + wo0) * SC_CO;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int e = tid + 256 * jj;
+            const int px = e >> 3, c = e & 7;
+            uintx4 v = {0u, 0u, 0u, 0u};
+            if (px < valid) v = *reinterpret_cast<const uintx4*>(gsrc + px * SC_CO + c * 8);
+            *reinterpret_cast<uintx4*>(gt + px * GP + c * 16) = v;
+        }
+        // image rows, as in the forward kernel
+        constexpr int NL = (KH * PW + 255) / 256;
+#pragma unroll
+        for (int jj = 0; jj < NL; ++jj) {
+            const int e = tid + 256 * jj;
+            const int kh = e / PW, q = e - kh * PW;
+            const int hi = ho * 2 - p.pad + kh, wi = wi0 + q;
+            uintx2 v = {0u, 0u};
+            if (e < KH * PW && (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W)
+                v = *reinterpret_cast<const uintx2*>(p.xp + (((long long)n * p.H + hi) * p.W + wi) * 4);
+            if (e < KH * PW) patch[e] = v;
+        }
+        __syncthreads();
+
+#pragma unroll
+        for (int s = 0; s < SC_TILE / 16; ++s) {
+            const uintx2 g0 = lds_read_tr_b64(gbase + 16 * s * GP), g1 = lds_read_tr_b64(gbase + (16 * s + 4) * GP);
+            const bf16x8 gf = __builtin_bit_cast(bf16x8, uintx4{g0[0], g0[1], g1[0], g1[1]});
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                const int kh = khs + 2 * u;          // wave-uniform
+                if (kh < KH) {
+                    const unsigned char* a = pbase + kh * PW * 8 + 16 * s * 16;
+                    const uintx2 p0 = lds_read_tr_b64(a), p1 = lds_read_tr_b64(a + 64);
+                    const bf16x8 pf = __builtin_bit_cast(bf16x8, uintx4{p0[0], p0[1], p1[0], p1[1]});
+                    acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, gf, acc[u], 0, 0, 0);
+                }
+            }
+            if (khs == 1) accs = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, gf, accs, 0, 0, 0);
+        }
+    }
+
+    // partial of this workgroup: [co][SC_PK], lane = channel (lane & 31), 4 consecutive k' per register group
+    float* part = p.partial + (long long)blockIdx.x * SC_CO * SC_PK + (long long)(32 * cot + (lane & 31)) * SC_PK;
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+        const int kh = khs + 2 * u;
+        if (kh < KH) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                *reinterpret_cast<floatx4*>(part + kh * 32 + 8 * g + 4 * (lane >> 5)) =
+                    floatx4{acc[u][4 * g], acc[u][4 * g + 1], acc[u][4 * g + 2], acc[u][4 * g + 3]};
+        }
+    }
+    if (khs == 1 && lane < 32) part[256] = accs[0];   // every row of the ones-product is the column sum
+}
+
+// One workgroup per output channel: fixed-order sum over the partials, dW = scale * G on the real taps and
+// channels, dscale = <W[co,:], G[co,:]>, dshift = sum of the column sums.
+__global__ __launch_bounds__(256) void smallc_wgrad_reduce_kernel(const SmallCWgradParams p) {
+    __shared__ float red[256];
+    const int co = blockIdx.x, tid = threadIdx.x;
+    const float* src = p.partial + (long long)co * SC_PK + tid;
+    const long long stride = (long long)SC_CO * SC_PK;
+    float g = 0.f;
+    if (tid < 32 * p.KH) {
+        int b = 0;
+        for (; b + 8 <= p.nparts; b += 8) {
+            float a[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a[u] = src[(b + u) * stride];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) g += a[u];
+        }
+        for (; b < p.nparts; ++b) g += src[b * stride];
+    }
+    float dot = 0.f;
+    const int kh = tid >> 5, kw = (tid & 31) >> 2, ci = tid & 3;
+    if (tid < 32 * p.KH && kw < p.KW && ci < p.C_in) {
+        const long long o = (((long long)co * p.KH + kh) * p.KW + kw) * p.C_in + ci;
+        dot = bf16_to_f32(p.Wt[o]) * g;
+        const float d = p.scale[co] * g;
+        p.dW[o] = p.accumulate ? p.dW[o] + d : d;
+    }
+    // dshift: the threads share the partials' column sums, then a fixed-order tree over the workgroup
+    float mine = 0.f;
+    for (int b = tid; b < p.nparts; b += 256) mine += p.partial[b * stride + (long long)co * SC_PK + 256];
+    red[tid] = dot;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (tid < o) red[tid] += red[tid + o];
+        __syncthreads();
+    }
+    const float ds = red[0];
+    __syncthreads();
+    red[tid] = mine;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (tid < o) red[tid] += red[tid + o];
+        __syncthreads();
+    }
+    if (tid == 0) {
+        p.dscale[co] = p.accumulate ? p.dscale[co] + ds : ds;
+        p.dshift[co] = p.accumulate ? p.dshift[co] + red[0] : red[0];
+    }
+}
+
+int smallc_wgrad_parts(int N, int Ho, int Wo) {
+    const long long tiles = (long long)N * Ho * ((Wo + SC_TILE - 1) / SC_TILE);
+    return (int)(tiles < 256 ? tiles : 256);         // one workgroup per compute unit keeps the partials small
+}
+size_t smallc_wgrad_partial_bytes(int nparts) { return (size_t)nparts * SC_CO * SC_PK * 4; }
+
+template <int KH>
+static hipError_t launch_smallc_wgrad_kh(const SmallCWgradParams& p, hipStream_t stream) {
+    hipLaunchKernelGGL(smallc_wgrad_kernel<KH>, dim3(p.nparts), dim3(256), 0, stream, p);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    hipLaunchKernelGGL(smallc_wgrad_reduce_kernel, dim3(SC_CO), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_smallc_wgrad(const SmallCWgradParams& p, hipStream_t stream) {
+    switch (p.KH) {
+        case 1: return launch_smallc_wgrad_kh<1>(p, stream);
+        case 2: return launch_smallc_wgrad_kh<2>(p, stream);
+        case 3: return launch_smallc_wgrad_kh<3>(p, stream);
+        case 4: return launch_smallc_wgrad_kh<4>(p, stream);
+        case 5: return launch_smallc_wgrad_kh<5>(p, stream);
+        case 6: return launch_smallc_wgrad_kh<6>(p, stream);
+        case 7: return launch_smallc_wgrad_kh<7>(p, stream);
+        case 8: return launch_smallc_wgrad_kh<8>(p, stream);
         default: return hipErrorInvalidValue;
     }
 }

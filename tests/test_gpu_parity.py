@@ -171,6 +171,22 @@ def test_data_and_weight_branch_as_two_calls(shape):
     show(f"two calls {shape}", pu.check_block(case, two))
 
 
+@pytest.mark.parametrize("shape", [
+    dict(N=2, H=30, W=530, C_in=3, C_out=64, K=7, stride=2, pad=3),            # stem: 3 row segments, ragged
+    dict(N=3, H=9, W=11, C_in=4, C_out=64, K=3, stride=2, pad=1),              # 3x3, 4 channels: only filter rows 0..2
+    dict(N=1, H=16, W=16, C_in=1, C_out=64, K=5, stride=2, pad=2),             # 1 channel
+    dict(N=5, H=64, W=64, C_in=3, C_out=64, K=7, stride=2, pad=3),             # more row segments than workgroups share evenly
+])
+def test_few_channel_weight_gradient(shape):
+    """The stem's own weight-gradient kernels (gradient masked upstream, no data gradient), including accumulation."""
+    case = pu.make_case(41, **shape)
+    got = pu.gpu_block(case, need_dx=False, premasked=True)
+    show(f"few-channel wgrad {shape}", pu.check_block(case, got, need_dx=False, premasked=True))
+    again = pu.gpu_block(case, need_dx=False, premasked=True)
+    for k in ("dW", "dscale", "dshift"):
+        assert np.array_equal(got[k], again[k]), k
+
+
 def test_runs_are_bitwise_reproducible():
     case = pu.make_case(13, 2, 28, 28, 64, 128, 3, 1, 1, res=True)
     a, b = pu.gpu_block(case), pu.gpu_block(case)
