@@ -172,7 +172,7 @@ BwdPlan plan_bwd(const sol_block_desc* d, const Geometry& g) {
     }
     b.dshift_off = b.part_off + align_up((size_t)b.splits * g.w_elems * 4);
     b.total = b.dshift_off + align_up((size_t)b.splits * d->C_out * 4);
-    b.smallc = d->dtype == SOL_BF16 && smallc_fwd_supported(d->C_in, d->C_out, d->KH, d->KW, d->stride) &&
+    b.smallc = d->dtype == SOL_BF16 && smallc_wgrad_supported(d->C_in, d->C_out, d->KH, d->KW, d->stride) &&
                env_int("SOL_SMALLC", 1) != 0;
     if (b.smallc) {
         b.sc_parts = smallc_wgrad_parts(d->N, g.Ho, g.Wo);

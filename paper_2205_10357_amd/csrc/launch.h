@@ -57,6 +57,7 @@ struct SmallCWgradParams {     // weight gradient of the same layers (dy already
     float* dshift;
     int N, H, W, C_in, KH, KW, pad, Ho, Wo, nparts, accumulate;
 };
+bool smallc_wgrad_supported(int C_in, int C_out, int KH, int KW, int stride);
 int smallc_wgrad_parts(int N, int Ho, int Wo);
 size_t smallc_wgrad_partial_bytes(int nparts);
 hipError_t launch_smallc_wgrad(const SmallCWgradParams& p, hipStream_t stream);

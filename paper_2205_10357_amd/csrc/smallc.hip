@@ -234,151 +234,185 @@ hipError_t launch_smallc_fwd(const SmallCParams& p, hipStream_t stream) {
 // per 16 lanes a 4 x 16 block, 4 reduction rows x 16 columns).  A workgroup keeps its accumulators over all the
 // row segments it processes and writes one fp32 partial [64 co][264] (32*KH gradient columns, column 256 = the
 // column sum of g, i.e. dshift) at the end; smallc_wgrad_reduce_kernel adds the workgroups in a fixed order.
-// Waves: channel tile (wave & 1) x filter rows {kh : kh % 2 == wave / 2}; the odd-row waves also own dshift.
+// Wave w owns filter-row slots 2w and 2w+1 for both channel tiles (2 x 2 register blocking: 8 transposing reads per
+// 4 MFMAs); a slot without a filter row multiplies all-ones instead, and slot 7 (never a filter row) yields dshift.
 template <int KH>
 __global__ __launch_bounds__(256) void smallc_wgrad_kernel(const SmallCWgradParams p) {
     constexpr int PW = SC_TILE * 2 + 8;
     constexpr int GP = 160;                          // bytes per staged gradient row (128 + 32: the 4 rows of a
                                                      // transposing read fall into different banks)
-    constexpr int NU = 4;                            // filter rows per wave (kh = khs + 2*u)
+    static_assert(KH <= 7, "filter-row slot 7 must be free for the column sums");
     __shared__ __align__(16) uintx2 patch[KH * PW];
     __shared__ __align__(16) unsigned char gt[SC_TILE * GP];
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // wave-uniform: the filter-row tests below are scalar
-    const int cot = wave & 1, khs = wave >> 1;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int grp = lane >> 4, j = lane & 15;
     const int segs = (p.Wo + SC_TILE - 1) / SC_TILE;
     const int tiles = p.N * p.Ho * segs;
 
-    floatx16 acc[NU], accs;
+    // wave w owns filter-row slots 2w and 2w+1 for both channel tiles: acc[slot][channel tile]
+    floatx16 acc[2][2];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
+    for (int v = 0; v < 16; ++v)
 #pragma unroll
-        for (int u = 0; u < NU; ++u) acc[u][v] = 0.f;
-        accs[v] = 0.f;
-    }
-    bf16x8 ones;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
+        for (int u = 0; u < 2; ++u) acc[u][0][v] = acc[u][1][v] = 0.f;
 
     // lane part of the transposing-read addresses (reduction row 8*(grp>>1) + (j>>2), column piece 16*(grp&1) + 4*(j&3))
     const int mrow = 8 * (grp >> 1) + (j >> 2);
-    const unsigned char* gbase = gt + mrow * GP + (32 * cot + 16 * (grp & 1) + 4 * (j & 3)) * 2;
+    const unsigned char* gbase = gt + mrow * GP + (16 * (grp & 1) + 4 * (j & 3)) * 2;
     const unsigned char* pbase = reinterpret_cast<const unsigned char*>(patch) + mrow * 16 + 32 * (grp & 1) + 8 * (j & 3);
+    // A slot whose filter row does not exist multiplies an all-ones operand instead (its reads go to the last real
+    // row and are discarded): the step loop then has no branch, and the ones-product is the column sum of g.
+    const unsigned char* prow[2];
+    bool use_ones[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int kh = 2 * wave + u;
+        use_ones[u] = kh >= KH;
+        prow[u] = pbase + (kh < KH ? kh : KH - 1) * PW * 8;
+    }
 
-    for (int t = blockIdx.x; t < tiles; t += gridDim.x) {
+    // the operands of a tile as fetched by this thread: 4 gradient pieces (16 bytes) and NL image pixels (8 bytes)
+    constexpr int NL = (KH * PW + 255) / 256;
+    auto fetch = [&](int t, uintx4 (&gv)[4], uintx2 (&xv)[NL]) {
         const int seg = t % segs, row = t / segs;
         const int ho = row % p.Ho, n = row / p.Ho;
         const int wo0 = seg * SC_TILE;
         const int wi0 = wo0 * 2 - p.pad;
         const int valid = p.Wo - wo0 < SC_TILE ? p.Wo - wo0 : SC_TILE;
-        __syncthreads();                             // the previous tile has been read
-        // gradient rows: 128 pixels x 64 channels, 16-byte pieces; rows past the end of the image row are zero
+        // gradient rows: 128 pixels x 64 channels; rows past the end of the image row are zero
         const bf16_t* gsrc = p.dy + (((long long)n * p.Ho + ho) * p.Wo + wo0) * SC_CO;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             const int e = tid + 256 * jj;
             const int px = e >> 3, c = e & 7;
-            uintx4 v = {0u, 0u, 0u, 0u};
-            if (px < valid) v = *reinterpret_cast<const uintx4*>(gsrc + px * SC_CO + c * 8);
-            *reinterpret_cast<uintx4*>(gt + px * GP + c * 16) = v;
+            gv[jj] = uintx4{0u, 0u, 0u, 0u};
+            if (px < valid) gv[jj] = *reinterpret_cast<const uintx4*>(gsrc + px * SC_CO + c * 8);
         }
         // image rows, as in the forward kernel
-        constexpr int NL = (KH * PW + 255) / 256;
 #pragma unroll
         for (int jj = 0; jj < NL; ++jj) {
             const int e = tid + 256 * jj;
             const int kh = e / PW, q = e - kh * PW;
             const int hi = ho * 2 - p.pad + kh, wi = wi0 + q;
-            uintx2 v = {0u, 0u};
+            xv[jj] = uintx2{0u, 0u};
             if (e < KH * PW && (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W)
-                v = *reinterpret_cast<const uintx2*>(p.xp + (((long long)n * p.H + hi) * p.W + wi) * 4);
-            if (e < KH * PW) patch[e] = v;
+                xv[jj] = *reinterpret_cast<const uintx2*>(p.xp + (((long long)n * p.H + hi) * p.W + wi) * 4);
+        }
+    };
+
+    uintx4 gnext[4];
+    uintx2 xnext[NL];
+    int t = blockIdx.x;
+    if (t < tiles) fetch(t, gnext, xnext);
+    for (; t < tiles; t += gridDim.x) {
+        __syncthreads();                             // the previous tile has been read
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int e = tid + 256 * jj;
+            *reinterpret_cast<uintx4*>(gt + (e >> 3) * GP + (e & 7) * 16) = gnext[jj];
+        }
+#pragma unroll
+        for (int jj = 0; jj < NL; ++jj) {
+            const int e = tid + 256 * jj;
+            if (e < KH * PW) patch[e] = xnext[jj];
         }
         __syncthreads();
+        if (t + (int)gridDim.x < tiles) fetch(t + gridDim.x, gnext, xnext);   // in flight during this tile's arithmetic
 
 #pragma unroll
-        for (int s = 0; s < SC_TILE / 16; ++s) {
-            const uintx2 g0 = lds_read_tr_b64(gbase + 16 * s * GP), g1 = lds_read_tr_b64(gbase + (16 * s + 4) * GP);
-            const bf16x8 gf = __builtin_bit_cast(bf16x8, uintx4{g0[0], g0[1], g1[0], g1[1]});
+        for (int s = 0; s < SC_TILE / 16; ++s) {     // no branch in here: see `use_ones`
+            bf16x8 gf[2], pf[2];
 #pragma unroll
-            for (int u = 0; u < NU; ++u) {
-                const int kh = khs + 2 * u;          // wave-uniform
-                if (kh < KH) {
-                    const unsigned char* a = pbase + kh * PW * 8 + 16 * s * 16;
-                    const uintx2 p0 = lds_read_tr_b64(a), p1 = lds_read_tr_b64(a + 64);
-                    const bf16x8 pf = __builtin_bit_cast(bf16x8, uintx4{p0[0], p0[1], p1[0], p1[1]});
-                    acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, gf, acc[u], 0, 0, 0);
-                }
+            for (int c = 0; c < 2; ++c) {
+                const unsigned char* a = gbase + 16 * s * GP + 64 * c;
+                const uintx2 g0 = lds_read_tr_b64(a), g1 = lds_read_tr_b64(a + 4 * GP);
+                gf[c] = __builtin_bit_cast(bf16x8, uintx4{g0[0], g0[1], g1[0], g1[1]});
             }
-            if (khs == 1) accs = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, gf, accs, 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const unsigned char* a = prow[u] + 16 * s * 16;
+                const uintx2 p0 = lds_read_tr_b64(a), p1 = lds_read_tr_b64(a + 64);
+                uintx4 pv = {p0[0], p0[1], p1[0], p1[1]};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pv[e] = use_ones[u] ? 0x3f803f80u : pv[e];
+                pf[u] = __builtin_bit_cast(bf16x8, pv);
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+                    acc[u][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[u], gf[c], acc[u][c], 0, 0, 0);
         }
     }
 
     // partial of this workgroup: [co][SC_PK], lane = channel (lane & 31), 4 consecutive k' per register group
-    float* part = p.partial + (long long)blockIdx.x * SC_CO * SC_PK + (long long)(32 * cot + (lane & 31)) * SC_PK;
 #pragma unroll
-    for (int u = 0; u < NU; ++u) {
-        const int kh = khs + 2 * u;
-        if (kh < KH) {
+    for (int c = 0; c < 2; ++c) {
+        float* part = p.partial + (long long)blockIdx.x * SC_CO * SC_PK + (long long)(32 * c + (lane & 31)) * SC_PK;
 #pragma unroll
-            for (int g = 0; g < 4; ++g)
-                *reinterpret_cast<floatx4*>(part + kh * 32 + 8 * g + 4 * (lane >> 5)) =
-                    floatx4{acc[u][4 * g], acc[u][4 * g + 1], acc[u][4 * g + 2], acc[u][4 * g + 3]};
+        for (int u = 0; u < 2; ++u) {
+            const int kh = 2 * wave + u;
+            if (kh < KH) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    *reinterpret_cast<floatx4*>(part + kh * 32 + 8 * g + 4 * (lane >> 5)) =
+                        floatx4{acc[u][c][4 * g], acc[u][c][4 * g + 1], acc[u][c][4 * g + 2], acc[u][c][4 * g + 3]};
+            }
         }
+        // slot 7 (wave 3, u = 1) never has a filter row: every row of its ones-product is the column sum of g
+        if (wave == 3 && lane < 32) part[256] = acc[1][c][0];
     }
-    if (khs == 1 && lane < 32) part[256] = accs[0];   // every row of the ones-product is the column sum
 }
 
-// One workgroup per output channel: fixed-order sum over the partials, dW = scale * G on the real taps and
-// channels, dscale = <W[co,:], G[co,:]>, dshift = sum of the column sums.
-__global__ __launch_bounds__(256) void smallc_wgrad_reduce_kernel(const SmallCWgradParams p) {
+// One workgroup of 1024 threads per output channel: thread (q, k') sums every fourth partial of column k' (more
+// loads in flight than 256 threads give), the four sums are added in a fixed order; dW = scale * G on the real
+// taps and channels, dscale = <W[co,:], G[co,:]>, dshift = sum of the column sums (column 256, thread 255).
+__global__ __launch_bounds__(1024) void smallc_wgrad_reduce_kernel(const SmallCWgradParams p) {
+    __shared__ float quarter[4][SC_PK];
     __shared__ float red[256];
-    const int co = blockIdx.x, tid = threadIdx.x;
-    const float* src = p.partial + (long long)co * SC_PK + tid;
+    const int co = blockIdx.x, tid = threadIdx.x & 255, q = threadIdx.x >> 8;
     const long long stride = (long long)SC_CO * SC_PK;
-    float g = 0.f;
-    if (tid < 32 * p.KH) {
-        int b = 0;
-        for (; b + 8 <= p.nparts; b += 8) {
+    const bool col_ok = tid < 32 * p.KH || tid == 255;
+    const int col = tid == 255 ? 256 : tid;
+    if (col_ok) {
+        const float* src = p.partial + (long long)co * SC_PK + col;
+        float g = 0.f;
+        int b = q;
+        for (; b + 28 < p.nparts; b += 32) {           // 8 loads in flight, fixed add order
             float a[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) a[u] = src[(b + u) * stride];
+            for (int u = 0; u < 8; ++u) a[u] = src[(b + 4 * u) * stride];
 #pragma unroll
             for (int u = 0; u < 8; ++u) g += a[u];
         }
-        for (; b < p.nparts; ++b) g += src[b * stride];
+        for (; b < p.nparts; b += 4) g += src[b * stride];
+        quarter[q][col] = g;
     }
-    float dot = 0.f;
+    __syncthreads();
+    float g = 0.f, dot = 0.f;
+    if (q == 0 && col_ok) g = (quarter[0][col] + quarter[1][col]) + (quarter[2][col] + quarter[3][col]);
     const int kh = tid >> 5, kw = (tid & 31) >> 2, ci = tid & 3;
-    if (tid < 32 * p.KH && kw < p.KW && ci < p.C_in) {
+    if (q == 0 && tid < 32 * p.KH && kw < p.KW && ci < p.C_in) {
         const long long o = (((long long)co * p.KH + kh) * p.KW + kw) * p.C_in + ci;
         dot = bf16_to_f32(p.Wt[o]) * g;
         const float d = p.scale[co] * g;
         p.dW[o] = p.accumulate ? p.dW[o] + d : d;
     }
-    // dshift: the threads share the partials' column sums, then a fixed-order tree over the workgroup
-    float mine = 0.f;
-    for (int b = tid; b < p.nparts; b += 256) mine += p.partial[b * stride + (long long)co * SC_PK + 256];
-    red[tid] = dot;
+    if (q == 0) red[tid] = dot;
     __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
-        if (tid < o) red[tid] += red[tid + o];
-        __syncthreads();
+    if (q == 0 && tid < 64) {
+        float v = (red[tid] + red[tid + 64]) + (red[tid + 128] + red[tid + 192]);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+        if (tid == 0) p.dscale[co] = p.accumulate ? p.dscale[co] + v : v;
     }
-    const float ds = red[0];
-    __syncthreads();
-    red[tid] = mine;
-    __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
-        if (tid < o) red[tid] += red[tid + o];
-        __syncthreads();
-    }
-    if (tid == 0) {
-        p.dscale[co] = p.accumulate ? p.dscale[co] + ds : ds;
-        p.dshift[co] = p.accumulate ? p.dshift[co] + red[0] : red[0];
-    }
+    if (q == 0 && tid == 255) p.dshift[co] = p.accumulate ? p.dshift[co] + g : g;
+}
+
+bool smallc_wgrad_supported(int C_in, int C_out, int KH, int KW, int stride) {
+    return smallc_fwd_supported(C_in, C_out, KH, KW, stride) && KH <= 7;
 }
 
 int smallc_wgrad_parts(int N, int Ho, int Wo) {
@@ -391,7 +425,7 @@ template <int KH>
 static hipError_t launch_smallc_wgrad_kh(const SmallCWgradParams& p, hipStream_t stream) {
     hipLaunchKernelGGL(smallc_wgrad_kernel<KH>, dim3(p.nparts), dim3(256), 0, stream, p);
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
-    hipLaunchKernelGGL(smallc_wgrad_reduce_kernel, dim3(SC_CO), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL(smallc_wgrad_reduce_kernel, dim3(SC_CO), dim3(1024), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -404,7 +438,6 @@ hipError_t launch_smallc_wgrad(const SmallCWgradParams& p, hipStream_t stream) {
         case 5: return launch_smallc_wgrad_kh<5>(p, stream);
         case 6: return launch_smallc_wgrad_kh<6>(p, stream);
         case 7: return launch_smallc_wgrad_kh<7>(p, stream);
-        case 8: return launch_smallc_wgrad_kh<8>(p, stream);
         default: return hipErrorInvalidValue;
     }
 }
