@@ -81,6 +81,7 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, hipStream_t stre
     const bool fast_ok = !mask && few_taps && (p.Cs % 64) == 0 && (p.Nc % 8) == 0 &&
                          env_int("SOL_IGEMM_FAST", 1) != 0;
     int bp, bc, tile = 0, stages = 0;
+    bool many_tiles = false;
     if (fast_ok) {
         long long slices = 0;
         for (int c = 0; c < p.ncls; ++c) {
@@ -97,6 +98,11 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, hipStream_t stre
             // short reductions are dominated by per-workgroup latency (prologue, epilogue): many small
             // workgroups per compute unit hide it better than few large ones
             if (slices <= env_int("SOL_FAST_SHORTK", 4) && t128 >= 512) tile = 2;
+            // many tiles per compute unit: 128 x 64 tiles with two stages leave room for three workgroups per
+            // compute unit, whose prologues and epilogues overlap (measured over the ResNet-50 layer shapes:
+            // best or within a few percent of best from ~3 tiles of 128 x 128 per compute unit upwards)
+            many_tiles = t128 >= env_int("SOL_FAST_MANY", 700);
+            if (many_tiles) tile = 1;
             long long t = 0;
             igemm_fast_tile_shape(tile, &bp, &bc);
             for (int c = 0; c < p.ncls; ++c) t += (rows[c] + bp - 1) / bp;
@@ -104,7 +110,7 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, hipStream_t stre
             if (t < 160) tile = 2;
         }
         stages = env_int("SOL_FAST_STAGES", 0);
-        if (stages < 2 || stages > 4) stages = slices <= 4 ? 2 : (slices <= 8 ? 3 : 4);
+        if (stages < 2 || stages > 4) stages = (slices <= 4 || many_tiles) ? 2 : (slices <= 8 ? 3 : 4);
         if (tile == 3 && stages > 3) stages = 3;
         igemm_fast_tile_shape(tile, &bp, &bc);
     } else {
