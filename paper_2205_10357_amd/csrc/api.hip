@@ -101,7 +101,7 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, hipStream_t stre
             // many tiles per compute unit: 128 x 64 tiles with two stages leave room for three workgroups per
             // compute unit, whose prologues and epilogues overlap (measured over the ResNet-50 layer shapes:
             // best or within a few percent of best from ~3 tiles of 128 x 128 per compute unit upwards)
-            many_tiles = t128 >= env_int("SOL_FAST_MANY", 700);
+            many_tiles = t128 >= env_int("SOL_FAST_MANY", 700) * (slices <= 4 ? 2 : 1);   // short reductions: 64 x 64 holds up longer
             if (many_tiles) tile = 1;
             long long t = 0;
             igemm_fast_tile_shape(tile, &bp, &bc);
@@ -280,6 +280,10 @@ int dgrad_bf16(const sol_block_desc* d, const Geometry& g, const void* dy, const
     p.relu = 0;
     long long rows[kMaxClasses];
     int nc = 0;
+    // pixels without a tap (1x1 / stride 2: three quarters of dx) are filled at memory speed by a launch of their
+    // own; as GEMM tiles without a reduction they cost several times that
+    const bool fill_untouched = (d->C_in % 8) == 0 && env_int("SOL_FILL_UNTOUCHED", 1) != 0;
+    bool any_untouched = false;
     for (int ph = 0; ph < s; ++ph)
         for (int pw = 0; pw < s; ++pw) {
             const int Rh = d->H > ph ? (d->H - ph + s - 1) / s : 0;
@@ -290,6 +294,10 @@ int dgrad_bf16(const sol_block_desc* d, const Geometry& g, const void* dy, const
             c.Th = class_taps(d->KH, s, d->pad, ph, &fh);
             c.Tw = class_taps(d->KW, s, d->pad, pw, &fw);
             if (c.Th == 0 || c.Tw == 0) {   // no tap reaches these pixels: K = 0, output = addend
+                if (fill_untouched) {       // ... written by an element-wise launch instead of GEMM tiles
+                    any_untouched = true;
+                    continue;
+                }
                 c.Th = 0;
                 c.Tw = 1;
             }
@@ -310,6 +318,10 @@ int dgrad_bf16(const sol_block_desc* d, const Geometry& g, const void* dy, const
             ++nc;
         }
     p.ncls = nc;
+    if (any_untouched &&
+        launch_untouched_pixels(dx, addend, addend_mask, dx_mask, d->N, d->H, d->W, d->C_in, d->KH, d->KW, s, d->pad,
+                                stream) != hipSuccess)
+        return SOL_ERR_LAUNCH;
     return run_igemm(p, rows, relu, stream);
 }
 

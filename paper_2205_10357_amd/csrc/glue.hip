@@ -110,7 +110,40 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const void* xv, void* yv, 
     else reinterpret_cast<float*>(yv)[idx] = m;
 }
 
+// Data gradient of a strided block, input pixels that no filter tap reaches (1x1 / stride 2: three of four): their
+// gradient is the addend (optionally gated) or zero, then the optional output mask.  One thread per (pixel, 8
+// channels); pixels that some tap reaches belong to the GEMM launch and are left alone.
+__global__ __launch_bounds__(256) void untouched_pixels_kernel(bf16_t* dx, const bf16_t* addend, const bf16_t* addend_mask,
+                                                               const bf16_t* out_mask, int N, int H, int W, int C, int KH,
+                                                               int KW, int stride, int pad) {
+    const int c8 = C >> 3;
+    const long long total = (long long)N * H * W * c8;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const long long pix = idx / c8;
+    const int wi = (int)(pix % W), hi = (int)((pix / W) % H);
+    int f;
+    if (class_taps(KH, stride, pad, hi % stride, &f) > 0 && class_taps(KW, stride, pad, wi % stride, &f) > 0) return;
+    uintx4 v = {0u, 0u, 0u, 0u};
+    if (addend) {
+        v = *reinterpret_cast<const uintx4*>(addend + idx * 8);
+        if (addend_mask) v = mask_where_positive(v, *reinterpret_cast<const uintx4*>(addend_mask + idx * 8));
+    }
+    if (out_mask) v = mask_where_positive(v, *reinterpret_cast<const uintx4*>(out_mask + idx * 8));
+    *reinterpret_cast<uintx4*>(dx + idx * 8) = v;
+}
+
 static inline unsigned blocks_for(long long total) { return (unsigned)((total + 255) / 256); }
+
+hipError_t launch_untouched_pixels(void* dx, const void* addend, const void* addend_mask, const void* out_mask, int N,
+                                   int H, int W, int C, int KH, int KW, int stride, int pad, hipStream_t s) {
+    const long long total = (long long)N * H * W * (C >> 3);
+    if (total <= 0) return hipSuccess;
+    hipLaunchKernelGGL(untouched_pixels_kernel, dim3(blocks_for(total)), dim3(256), 0, s, (bf16_t*)dx,
+                       (const bf16_t*)addend, (const bf16_t*)addend_mask, (const bf16_t*)out_mask, N, H, W, C, KH, KW,
+                       stride, pad);
+    return hipGetLastError();
+}
 
 hipError_t launch_pack_dgrad_weights(const PackParams& p, hipStream_t s) {
     const long long total = (long long)p.C_out * p.KH * p.KW * p.C_in;

@@ -78,6 +78,8 @@ hipError_t launch_direct_fwd_f32(const DirectParams& p, hipStream_t s);
 hipError_t launch_direct_dgrad_f32(const DirectParams& p, hipStream_t s);
 hipError_t launch_direct_wgrad_f32(const DirectParams& p, hipStream_t s);
 hipError_t launch_pack_dgrad_weights(const PackParams& p, hipStream_t s);
+hipError_t launch_untouched_pixels(void* dx, const void* addend, const void* addend_mask, const void* out_mask, int N,
+                                   int H, int W, int C, int KH, int KW, int stride, int pad, hipStream_t s);
 hipError_t launch_masked_copy(int dtype, const void* dy, const void* y, void* dres, long long numel, hipStream_t s);
 hipError_t launch_l1_grad(int dtype, const void* y, const void* t, void* dy, long long numel, int mask_by_y,
                           hipStream_t s);
