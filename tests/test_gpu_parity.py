@@ -140,6 +140,7 @@ def test_bf16_addend_mask_and_accumulate():
     dict(N=2, H=14, W=14, C_in=64, C_out=128, K=3, stride=1, pad=1, res=True),      # pipelined kernel
     dict(N=2, H=14, W=14, C_in=128, C_out=64, K=1, stride=1, pad=0),
     dict(N=2, H=15, W=13, C_in=64, C_out=64, K=3, stride=2, pad=1),
+    dict(N=2, H=15, W=13, C_in=64, C_out=128, K=1, stride=2, pad=0, relu=False),    # 3 of 4 pixels see no tap: fill launch
     dict(N=1, H=9, W=9, C_in=24, C_out=40, K=3, stride=1, pad=1),                   # general kernel
     dict(N=1, H=8, W=8, C_in=8, C_out=8, K=3, stride=1, pad=1, bf16=False),          # fp32 path
 ])
@@ -185,6 +186,20 @@ def test_few_channel_weight_gradient(shape):
     again = pu.gpu_block(case, need_dx=False, premasked=True)
     for k in ("dW", "dscale", "dshift"):
         assert np.array_equal(got[k], again[k]), k
+
+
+def test_untouched_pixels_take_addend_and_masks():
+    """1x1 / stride 2: pixels no tap reaches get the (gated) addend and the output mask from the fill launch."""
+    case = pu.make_case(51, 2, 14, 14, 64, 128, 1, 2, 0, relu=False)
+    r = np.random.default_rng(52)
+    ad = wl.snap_to_bf16(r.standard_normal(case["x"].shape).astype(np.float32))
+    am = wl.snap_to_bf16(np.maximum(r.standard_normal(case["x"].shape), 0).astype(np.float32))
+    dxm = wl.snap_to_bf16(np.maximum(r.standard_normal(case["x"].shape), 0).astype(np.float32))
+    got = pu.gpu_block(case, addend=ad, addend_mask=am, dx_mask=dxm)
+    show("untouched pixels", pu.check_block(case, got, addend=ad, addend_mask=am, dx_mask=dxm))
+    expect = np.where((am > 0) & (dxm > 0), ad, 0.0)
+    assert np.array_equal(got["dx"][:, :, 1::2, :], expect[:, :, 1::2, :])      # odd rows: no tap, exact copy
+    assert np.array_equal(got["dx"][:, :, :, 1::2], expect[:, :, :, 1::2])
 
 
 def test_runs_are_bitwise_reproducible():
