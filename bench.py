@@ -180,7 +180,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "global_batch": n, "blocks": len(blocks),
                    "launch": "hip_graph" if args.launch == "graph" else "eager", "backward_lanes": lanes,
-                   "flop_per_step": flops, "pct_mfma_peak": round(100 * value / MFMA_BF16_PEAK_TFLOPS, 2)},
+                   "flop_per_step": flops, "pct_mfma_peak": round(100 * value / MFMA_BF16_PEAK_TFLOPS, 2),
+                   "memory_plan_bytes": seq.memory_report()},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                      "traffic": DOMINANT_KERNEL_TRAFFIC_BYTES.get((wl.name, n)), "traffic_unit": "bytes/launch",

@@ -122,6 +122,10 @@ class Sequencer:
                 self.dact[tid] = torch.empty((n, h, w, c), dtype=self.tdtype, device=self.device)
             self._plan_backward()
 
+    def memory_report(self) -> Dict[str, int]:
+        """Bytes of this schedule by kind of data (static: shapes and execution order only)."""
+        return self.wl.memory_plan(workspace_bytes=int(self.ws.numel()))
+
     # ------------------------------------------------------------------ forward
     def forward(self, stream=None) -> torch.Tensor:
         for o in self.ops:

@@ -231,6 +231,49 @@ class Workload:
         shp = self.tensor_shapes()
         return sum(conv_flops(self.n, shp[b.inp][1], shp[b.inp][2], b) for b in self.conv_blocks())
 
+    def memory_plan(self, workspace_bytes: int = 0) -> Dict[str, int]:
+        """Bytes of the static schedule by kind of data, known before the first run (the paper's section on
+        memory consumption estimates the peak the same way, from the execution order and the tensor sizes).
+
+        Training keeps every activation between the passes (the backward pass reads the block inputs and the
+        masks) and one gradient per activation; inference needs a tensor only until its last reader has run, so
+        its activation peak is the largest set of tensors alive at one op of the schedule (a residual keeps the
+        block input alive across the three convolutions)."""
+        es = 2 if self.dtype == "bf16" else 4
+        shp = self.tensor_shapes()
+        size = {t: self.n * c * h * w * es for t, (c, h, w) in shp.items()}
+        plan = {"input": size[0], "parameters": 0, "outputs": size[self.ops[-1].out]}
+        for b in self.conv_blocks():
+            c_in = shp[b.inp][0]
+            plan["parameters"] += b.c_out * b.k * b.k * c_in * es + 2 * b.c_out * 4
+        inter = [o.out for o in self.ops[:-1]]
+        plan["intermediates_all_kept"] = sum(size[t] for t in inter)
+        last_use = {0: 0}
+        for i, o in enumerate(self.ops):
+            last_use[o.inp] = i
+            if getattr(o, "res", None) is not None:
+                last_use[o.res] = i
+        peak = 0
+        for i, o in enumerate(self.ops):           # alive while op i runs: its output and everything still to be read
+            alive = size[o.out] + sum(size[t] for t, lu in last_use.items() if lu >= i and t != o.out and
+                                      (t == 0 or any(oo.out == t for oo in self.ops[:i])))
+            peak = max(peak, alive)
+        plan["inference_peak_activations"] = peak      # includes the input while it is alive
+        if self.train:
+            plan["target"] = size[self.ops[-1].out]
+            plan["parameter_gradients"] = sum(b.c_out * b.k * b.k * shp[b.inp][0] * 4 + 2 * b.c_out * 4
+                                              for b in self.conv_blocks())
+            plan["activation_gradients"] = sum(size[t] for t in shp if t != 0 or self.need_input_grad)
+        plan["workspace"] = int(workspace_bytes)
+        keep = ("input", "parameters", "outputs", "workspace")
+        if self.train:
+            plan["total_training"] = sum(plan[k] for k in keep) + plan["intermediates_all_kept"] + plan["target"] + \
+                plan["parameter_gradients"] + plan["activation_gradients"]
+        else:
+            plan["total_inference_all_kept"] = sum(plan[k] for k in keep) + plan["intermediates_all_kept"]
+            plan["total_inference_minimum"] = plan["parameters"] + plan["workspace"] + plan["inference_peak_activations"]
+        return plan
+
     def flops_step(self) -> int:
         """Forward only for inference; x3 for training, x2 for blocks whose dx is skipped."""
         if not self.train:

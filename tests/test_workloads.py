@@ -56,3 +56,27 @@ def test_snap_to_bf16_agrees_with_checker_quantiser():
     bits = wl.bf16_bits(s)
     assert bits.dtype == np.uint16
     assert np.array_equal((bits.astype(np.uint32) << 16).view(np.float32), s)
+
+
+def test_memory_plan_of_the_static_schedule():
+    """Bytes by kind, from shapes and execution order alone (hand-computed for the 14x14 bottleneck)."""
+    w3 = wl.Workload(3, "t", "bf16", 64, 14, 14, 1024, wl.bottleneck14_ops(), np.zeros((1,), np.float32))
+    m = w3.memory_plan(workspace_bytes=1000)
+    px = 64 * 14 * 14
+    assert m["input"] == px * 1024 * 2 and m["outputs"] == px * 1024 * 2 and m["target"] == px * 1024 * 2
+    assert m["intermediates_all_kept"] == 2 * px * 256 * 2
+    weights = 1024 * 256 + 9 * 256 * 256 + 256 * 1024
+    assert m["parameters"] == weights * 2 + 2 * 4 * (256 + 256 + 1024)
+    assert m["parameter_gradients"] == weights * 4 + 2 * 4 * (256 + 256 + 1024)
+    assert m["activation_gradients"] == px * (1024 + 256 + 256 + 1024) * 2
+    # inference: x stays alive for the shortcut; the peak is at the last block (x, a2, y)
+    assert m["inference_peak_activations"] == px * (1024 + 256 + 1024) * 2
+    assert m["workspace"] == 1000
+    # ResNet-50 inference at N = 128: the largest tensor is the stem output (205.5 MB); the peak holds it twice over
+    ops = wl.resnet50_ops()
+    w4 = wl.Workload(4, "t", "bf16", 128, 224, 224, 3, ops, np.zeros((1,), np.float32), train=False)
+    m4 = w4.memory_plan()
+    assert abs(max(128 * c * h * ww * 2 for c, h, ww in w4.tensor_shapes().values()) / 1e6 - 205.5) < 0.1
+    assert m4["inference_peak_activations"] < 0.3 * m4["intermediates_all_kept"]
+    assert abs(m4["parameters"] / 1e6 - (23.45 * 2 + 0.2)) < 0.3
+    assert "total_inference_minimum" in m4 and "total_training" not in m4
