@@ -38,20 +38,23 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-// Per 16-bit lane: keep v where the bf16 value m is > 0, else +0.   (bf16 > 0  <=>  the
-// pattern read as a signed 16-bit integer is > 0; NaNs do not occur in stored activations.)
-__device__ __forceinline__ uintx4 mask_where_positive(uintx4 v, uintx4 m) {
-    shortx8 ms = __builtin_bit_cast(shortx8, m);
-    shortx8 keep = ms > (short)0;            // all-ones / zero per lane
-    shortx8 vs = __builtin_bit_cast(shortx8, v);
-    return __builtin_bit_cast(uintx4, (shortx8)(vs & keep));
+// Per 16-bit lane: all-ones where the bf16 value m is > 0, else zero.  (bf16 > 0  <=>  the pattern
+// read as a signed 16-bit integer is > 0; NaNs do not occur in stored activations.)  Two packed
+// 16-bit instructions per dword: 0 - m with saturation is negative exactly for m > 0 (the
+// saturation keeps -32768, i.e. -0.0, from wrapping to itself), and the arithmetic shift spreads the sign.
+__device__ __forceinline__ uintx4 positive_lanes(uintx4 m) {
+    const shortx8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    const shortx8 neg = __builtin_elementwise_sub_sat(zero, __builtin_bit_cast(shortx8, m));
+    return __builtin_bit_cast(uintx4, (shortx8)(neg >> (short)15));
 }
-__device__ __forceinline__ uintx2 mask_where_positive(uintx2 v, uintx2 m) {
-    shortx4 ms = __builtin_bit_cast(shortx4, m);
-    shortx4 keep = ms > (short)0;
-    shortx4 vs = __builtin_bit_cast(shortx4, v);
-    return __builtin_bit_cast(uintx2, (shortx4)(vs & keep));
+__device__ __forceinline__ uintx2 positive_lanes(uintx2 m) {
+    const shortx4 zero = {0, 0, 0, 0};
+    const shortx4 neg = __builtin_elementwise_sub_sat(zero, __builtin_bit_cast(shortx4, m));
+    return __builtin_bit_cast(uintx2, (shortx4)(neg >> (short)15));
 }
+// Per 16-bit lane: keep v where the bf16 value m is > 0, else +0.
+__device__ __forceinline__ uintx4 mask_where_positive(uintx4 v, uintx4 m) { return v & positive_lanes(m); }
+__device__ __forceinline__ uintx2 mask_where_positive(uintx2 v, uintx2 m) { return v & positive_lanes(m); }
 
 // ---- asynchronous global -> LDS copies (16 bytes per lane, no register staging) -----------
 // The wave's 64 pieces land at lds_wave_base + 16 * lane; lds_wave_base must be wave-uniform.

@@ -27,6 +27,20 @@ __device__ __forceinline__ int fast_xcd_remap(int bid, int nblocks) {
     return start + idx;
 }
 
+// Pins "NC async copies and NM MFMAs" as copy, MFMA, copy, MFMA, ...: a copy holds the wave's issue
+// port for some twenty cycles, which one MFMA in flight covers and two copies in a row do not.
+template <int NC, int NM>
+__device__ __forceinline__ void fast_pin_copies_between_mfmas() {
+    constexpr int PAIRS = NC < NM ? NC : NM;
+#pragma unroll
+    for (int c = 0; c < PAIRS; ++c) {
+        __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    }
+    if constexpr (NC > PAIRS) __builtin_amdgcn_sched_group_barrier(0x010, NC - PAIRS, 0);
+    if constexpr (NM > PAIRS) __builtin_amdgcn_sched_group_barrier(0x008, NM - PAIRS, 0);
+}
+
 template <int BP, int BC, int WP, int WC, int NS>
 __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
     static_assert(WP * WC == 4, "four waves per workgroup");
@@ -249,22 +263,17 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
             }
             if constexpr (MORE) request_part(0, 3);
             multiply(1);
-            if constexpr (MORE && (LPS / 3) > 0) __builtin_amdgcn_sched_group_barrier(0x010, LPS / 3, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, TC * TP, 0);
+            fast_pin_copies_between_mfmas<MORE ? LPS / 3 : 0, TC * TP>();
             read_frags(1, st, 3);
             if constexpr (MORE) request_part(1, 3);
             multiply(0);
             __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);
-            if constexpr (MORE && (2 * LPS) / 3 - LPS / 3 > 0)
-                __builtin_amdgcn_sched_group_barrier(0x010, (2 * LPS) / 3 - LPS / 3, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, TC * TP, 0);
+            fast_pin_copies_between_mfmas<MORE ? (2 * LPS) / 3 - LPS / 3 : 0, TC * TP>();
             if constexpr (NEXT) read_frags(0, stn, 0);
             if constexpr (MORE) request_part(2, 3);
             multiply(1);
             if constexpr (NEXT) __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);
-            if constexpr (MORE && LPS - (2 * LPS) / 3 > 0)
-                __builtin_amdgcn_sched_group_barrier(0x010, LPS - (2 * LPS) / 3, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, TC * TP, 0);
+            fast_pin_copies_between_mfmas<MORE ? LPS - (2 * LPS) / 3 : 0, TC * TP>();
         };
 
         // slice 0 must have landed; slices 1 .. NS-2 may still be in flight if that many exist
@@ -295,9 +304,7 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
             __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);            // fragments of step 0
 #define SOL_SGB_STEP(KS)                                                                              \
             if constexpr ((KS) < 3) __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);              \
-            if constexpr (MORE && (((KS) + 1) * LPS) / 4 - ((KS) * LPS) / 4 > 0)                          \
-                __builtin_amdgcn_sched_group_barrier(0x010, (((KS) + 1) * LPS) / 4 - ((KS) * LPS) / 4, 0); \
-            __builtin_amdgcn_sched_group_barrier(0x008, TC * TP, 0);
+            fast_pin_copies_between_mfmas<MORE ? (((KS) + 1) * LPS) / 4 - ((KS) * LPS) / 4 : 0, TC * TP>();
             SOL_SGB_STEP(0)
             SOL_SGB_STEP(1)
             SOL_SGB_STEP(2)

@@ -202,6 +202,27 @@ def test_untouched_pixels_take_addend_and_masks():
     assert np.array_equal(got["dx"][:, :, :, 1::2], expect[:, :, :, 1::2])
 
 
+@pytest.mark.parametrize("shape", [
+    dict(N=8, H=23, W=23, C_in=64, C_out=256, K=1, stride=1, pad=0, res=True),          # forward: K = 64
+    dict(N=8, H=23, W=23, C_in=128, C_out=512, K=1, stride=1, pad=0, relu=False),       # K = 128, plain epilogue
+    dict(N=8, H=23, W=23, C_in=256, C_out=1024, K=1, stride=1, pad=0, res=True),        # K = 256
+    dict(N=8, H=23, W=23, C_in=512, C_out=256, K=1, stride=1, pad=0, res=True),         # K = 512
+    dict(N=8, H=23, W=23, C_in=256, C_out=64, K=1, stride=1, pad=0, relu=False),        # data gradient: K = 64 -> 256 channels
+    dict(N=8, H=23, W=23, C_in=1024, C_out=256, K=1, stride=1, pad=0, relu=False),      # data gradient: K = 256 -> 1024 channels
+])
+def test_pointwise_layers_with_short_reduction(shape):
+    """1x1 / stride 1 with a short reduction and >= 256 output channels (forward of an expand layer, data
+    gradient of a reduce layer): 4232 pixels, not a multiple of any tile height, many tiles per compute
+    unit's worth of workgroups.  The data gradient carries a gated addend and an output mask."""
+    case = pu.make_case(61, **shape)
+    r = np.random.default_rng(62)
+    dxm = wl.snap_to_bf16(np.maximum(r.standard_normal(case["x"].shape), 0).astype(np.float32))
+    ad = wl.snap_to_bf16(r.standard_normal(case["x"].shape).astype(np.float32))
+    am = wl.snap_to_bf16(np.maximum(r.standard_normal(case["x"].shape), 0).astype(np.float32))
+    got = pu.gpu_block(case, addend=ad, addend_mask=am, dx_mask=dxm, premasked=True)
+    show(f"pointwise {shape}", pu.check_block(case, got, addend=ad, addend_mask=am, dx_mask=dxm, premasked=True))
+
+
 def test_runs_are_bitwise_reproducible():
     case = pu.make_case(13, 2, 28, 28, 64, 128, 3, 1, 1, res=True)
     a, b = pu.gpu_block(case), pu.gpu_block(case)
