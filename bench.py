@@ -27,9 +27,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 
 # HBM bytes per launch of the dominant kernel on the default workload (3x3 forward convolution of the 14x14 bottleneck,
 # N = 64), from the FETCH_SIZE / WRITE_SIZE passes summarised in profiles/bottleneck14_bf16_step_counters.md:
-# 8012 KiB x 2.000 (copy-kernel scale) fetched + 6272 KiB written.  Valid for the kernel those passes ran; set to None
+# 8004.5 KiB x 2.000 (copy-kernel scale) fetched + 6272 KiB written.  Valid for the kernel those passes ran; set to None
 # whenever csrc/igemm_fast.hip or its launch heuristics change, until the passes are repeated.
-DOMINANT_KERNEL_TRAFFIC_BYTES = {("bottleneck14_bf16", 64): (8012 * 2.000 + 6272) * 1024}
+DOMINANT_KERNEL_TRAFFIC_BYTES = {("bottleneck14_bf16", 64): (8004.5 * 2.000 + 6272) * 1024}
 
 
 def parse():
