@@ -63,8 +63,12 @@ def download(t: torch.Tensor) -> np.ndarray:
 class Sequencer:
     """Device buffers + launch order for one workload."""
 
-    def __init__(self, wl: Workload, device="cuda:0"):
+    def __init__(self, wl: Workload, device="cuda:0", retain_activations: Optional[bool] = None):
+        """retain_activations: keep every activation in a buffer of its own.  Training always does (the
+        backward pass reads them); inference by default does not (None -> planned arena), unless a caller
+        wants to look at the intermediate tensors afterwards."""
         self.wl = wl
+        self.retain = wl.train or bool(retain_activations)
         self.device = torch.device(device)
         self.bf16 = wl.dtype == "bf16"
         self.sol_dtype = B.SOL_BF16 if self.bf16 else B.SOL_F32
@@ -74,9 +78,21 @@ class Sequencer:
         n = wl.n
         self.act: Dict[int, torch.Tensor] = {}        # NHWC activations
         self.act[0] = upload(nchw_to_nhwc(wl.x), self.tdtype, self.device)
-        for o in self.ops:
-            c, h, w = self.shapes[o.out]
-            self.act[o.out] = torch.empty((n, h, w, c), dtype=self.tdtype, device=self.device)
+        if self.retain:
+            # the backward pass reads every block input and every mask: one buffer per activation
+            for o in self.ops:
+                c, h, w = self.shapes[o.out]
+                self.act[o.out] = torch.empty((n, h, w, c), dtype=self.tdtype, device=self.device)
+        else:
+            # inference version of the schedule: nothing is retained, activations share one arena whose
+            # ranges are reused as soon as a tensor's last reader has run (planned from the static op order)
+            offsets, arena_bytes = wl.plan_inference_arena()
+            self.arena = torch.empty((max(arena_bytes, 256),), dtype=torch.uint8, device=self.device)
+            es = 2 if self.bf16 else 4
+            for o in self.ops:
+                c, h, w = self.shapes[o.out]
+                nbytes = n * h * w * c * es
+                self.act[o.out] = self.arena[offsets[o.out]:offsets[o.out] + nbytes].view(self.tdtype).view(n, h, w, c)
         self.params: Dict[int, Dict[str, torch.Tensor]] = {}
         self.desc: Dict[int, B.BlockDesc] = {}
         ws_bytes = 0
@@ -124,7 +140,10 @@ class Sequencer:
 
     def memory_report(self) -> Dict[str, int]:
         """Bytes of this schedule by kind of data (static: shapes and execution order only)."""
-        return self.wl.memory_plan(workspace_bytes=int(self.ws.numel()))
+        plan = self.wl.memory_plan(workspace_bytes=int(self.ws.numel()))
+        plan["activation_buffers_allocated"] = int(self.arena.numel()) if not self.retain else \
+            sum(int(t.numel()) * t.element_size() for k, t in self.act.items() if k != 0)
+        return plan
 
     # ------------------------------------------------------------------ forward
     def forward(self, stream=None) -> torch.Tensor:

@@ -22,7 +22,7 @@ Conventions
 from __future__ import annotations
 
 from dataclasses import dataclass, field
-from typing import Dict, List, Optional
+from typing import Dict, List, Optional, Tuple
 
 import numpy as np
 
@@ -270,9 +270,43 @@ class Workload:
             plan["total_training"] = sum(plan[k] for k in keep) + plan["intermediates_all_kept"] + plan["target"] + \
                 plan["parameter_gradients"] + plan["activation_gradients"]
         else:
+            plan["inference_arena"] = self.plan_inference_arena()[1]   # what the planned buffers really take (first fit)
             plan["total_inference_all_kept"] = sum(plan[k] for k in keep) + plan["intermediates_all_kept"]
             plan["total_inference_minimum"] = plan["parameters"] + plan["workspace"] + plan["inference_peak_activations"]
         return plan
+
+    def plan_inference_arena(self, align: int = 256) -> Tuple[Dict[int, int], int]:
+        """Byte offsets of the activations of an inference run inside one arena, and the arena's size.
+
+        The inference version of the schedule retains nothing for a backward pass (the paper generates the
+        inference and the training version of a network separately): a tensor occupies its bytes from the op
+        that writes it to its last reader, both included, so an op never writes over what it reads.  Placement
+        is the usual offline heuristic for such interval problems: largest tensor first, each at the lowest
+        offset where it meets no already placed tensor whose lifetime overlaps its own.  The network input
+        (tensor 0) is the caller's buffer and is not part of the arena; the final output lives to the end."""
+        es = 2 if self.dtype == "bf16" else 4
+        shp = self.tensor_shapes()
+        size = {t: -(-(self.n * c * h * w * es) // align) * align for t, (c, h, w) in shp.items() if t != 0}
+        born = {o.out: i for i, o in enumerate(self.ops)}
+        dies = dict(born)                                    # an output nobody reads dies where it is born
+        for i, o in enumerate(self.ops):
+            for t in (o.inp, getattr(o, "res", None)):
+                if t is not None and t != 0:
+                    dies[t] = i
+        dies[self.ops[-1].out] = len(self.ops)
+        offset: Dict[int, int] = {}
+        top = 0
+        for t in sorted(size, key=lambda t: (-size[t], born[t])):
+            busy = sorted((offset[u], offset[u] + size[u]) for u in offset
+                          if born[u] <= dies[t] and born[t] <= dies[u])
+            at = 0
+            for lo, hi in busy:
+                if at + size[t] <= lo:
+                    break
+                at = max(at, hi)
+            offset[t] = at
+            top = max(top, at + size[t])
+        return offset, top
 
     def flops_step(self) -> int:
         """Forward only for inference; x3 for training, x2 for blocks whose dx is skipped."""

@@ -223,6 +223,24 @@ def test_pointwise_layers_with_short_reduction(shape):
     show(f"pointwise {shape}", pu.check_block(case, got, addend=ad, addend_mask=am, dx_mask=dxm, premasked=True))
 
 
+def test_gates_treat_signed_zero_and_denormals_like_the_comparison():
+    """A gate lets a value through where the mask is > 0: -0.0 and +0.0 block, the smallest positive bf16
+    denormal passes, negative values (denormal, -inf) block, +inf passes."""
+    case = pu.make_case(71, 2, 14, 14, 64, 128, 1, 1, 0, relu=False)
+    r = np.random.default_rng(72)
+    specials = np.array([-0.0, 0.0, 1e-40, -1e-40, 1.0, -1.0, np.inf, -np.inf], dtype=np.float32)
+    pick = lambda: wl.snap_to_bf16(specials[r.integers(0, len(specials), size=case["x"].shape)])
+    am, dxm = pick(), pick()
+    assert (am == 0).any() and np.signbit(am[am == 0]).any() and (np.abs(am[am != 0]) < 1e-38).any()
+    ad = wl.snap_to_bf16(r.standard_normal(case["x"].shape).astype(np.float32))
+    got = pu.gpu_block(case, addend=ad, addend_mask=am, dx_mask=dxm, premasked=True)
+    show("special gates", pu.check_block(case, got, addend=ad, addend_mask=am, dx_mask=dxm, premasked=True))
+    assert np.all(got["dx"][~(dxm > 0)] == 0)
+    w0 = dict(case, w=np.zeros_like(case["w"]))                  # no convolution term: dx is the gated addend itself
+    got = pu.gpu_block(w0, addend=ad, addend_mask=am, dx_mask=dxm, premasked=True)
+    assert np.array_equal(got["dx"], np.where((am > 0) & (dxm > 0), ad, 0.0))
+
+
 def test_runs_are_bitwise_reproducible():
     case = pu.make_case(13, 2, 28, 28, 64, 128, 3, 1, 1, res=True)
     a, b = pu.gpu_block(case), pu.gpu_block(case)

@@ -50,7 +50,7 @@ def grad_source(w):
 
 # ----------------------------------------------------------------- element-by-element, small sizes
 def check_chain_elementwise(w):
-    seq = runner.Sequencer(w, "cuda:0")
+    seq = runner.Sequencer(w, "cuda:0", retain_activations=True)
     seq.step()
     torch.cuda.synchronize()
     n = w.n
@@ -143,7 +143,7 @@ def test_resnet50_small_elementwise():
 # ------------------------------------------------------------------------- full sizes, sampled
 def check_sampled(w, images, n_fwd=400, n_dx=300, dw_layers=(), n_dw=64, n_ch=2, seed=5):
     rng = np.random.default_rng(seed)
-    seq = runner.Sequencer(w, "cuda:0")
+    seq = runner.Sequencer(w, "cuda:0", retain_activations=True)
     seq.step()
     torch.cuda.synchronize()
     images = list(images)
@@ -241,7 +241,7 @@ def test_stage2_full_size_sampled():
 def test_two_lane_backward_matches_one_lane():
     """Weight branches on a second stream (block by block behind the gradient they read): same bits."""
     w = wl.stage2_train_bf16(n=2, hw=14)
-    seq = runner.Sequencer(w, "cuda:0")
+    seq = runner.Sequencer(w, "cuda:0", retain_activations=True)
     seq.step()
     torch.cuda.synchronize()
     ref = {k: {n: t.clone() for n, t in v.items()} for k, v in seq.grads.items()}
@@ -266,7 +266,7 @@ def test_graph_replays_match_eager():
     """A captured step (two lanes: weight branches as parallel branches of the graph) replayed several times,
     with eager work and synchronisations in between, gives the eager one-lane result bit for bit every time."""
     w = wl.bottleneck14_bf16(n=8)
-    seq = runner.Sequencer(w, "cuda:0")
+    seq = runner.Sequencer(w, "cuda:0", retain_activations=True)
     seq.step()
     torch.cuda.synchronize()
     ref = {k: v.clone() for k, v in seq.dact.items()}
@@ -285,3 +285,22 @@ def test_graph_replays_match_eager():
                 assert torch.equal(seq.dact[k], ref[k]), (it, k)
         for k in ref_dw:
             assert torch.equal(seq.grads[k]["dW"], ref_dw[k]), (it, k)
+
+
+@pytest.mark.parametrize("size", ["small", "full"])
+def test_inference_arena_gives_the_retained_run_bit_for_bit(size):
+    """The inference version of the schedule keeps its activations in one planned arena (ranges reused after a
+    tensor's last reader); its network output must equal, bit for bit, that of a run with one buffer per
+    tensor, whose every layer the tests above check against the CPU checker.  Two passes: the arena is dirty
+    from the first when the second starts."""
+    w = wl.resnet50_infer_bf16(n=2, hw=64) if size == "small" else wl.resnet50_infer_bf16()
+    kept = runner.Sequencer(w, "cuda:0", retain_activations=True)
+    ref = kept.forward().clone()
+    del kept
+    seq = runner.Sequencer(w, "cuda:0")
+    assert not seq.retain and seq.arena.numel() == w.plan_inference_arena()[1]
+    assert seq.memory_report()["activation_buffers_allocated"] == seq.arena.numel()
+    for _ in range(2):
+        out = seq.forward()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref)

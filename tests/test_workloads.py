@@ -80,3 +80,38 @@ def test_memory_plan_of_the_static_schedule():
     assert m4["inference_peak_activations"] < 0.3 * m4["intermediates_all_kept"]
     assert abs(m4["parameters"] / 1e6 - (23.45 * 2 + 0.2)) < 0.3
     assert "total_inference_minimum" in m4 and "total_training" not in m4
+
+
+def test_inference_arena_never_overlaps_live_tensors():
+    """Planned activation buffers of the inference schedule: at every op the tensors alive (written earlier
+    and still to be read, the op's own output, the final output) occupy disjoint byte ranges; an op's output
+    never shares bytes with its operands; the arena is no larger than keeping everything and no smaller than
+    the largest set of bytes alive at one op."""
+    for ops, (c, h, w) in ((wl.resnet50_ops(), (3, 224, 224)), (wl.bottleneck14_ops(), (1024, 14, 14)),
+                           (wl.stage2_ops(True), (256, 56, 56))):
+        n = 2
+        W = wl.Workload(9, "t", "bf16", n, h, w, c, ops, np.zeros((1,), np.float32), train=False)
+        offset, top = W.plan_inference_arena()
+        shp = W.tensor_shapes()
+        nbytes = {t: n * cc * hh * ww * 2 for t, (cc, hh, ww) in shp.items()}
+        assert set(offset) == set(shp) - {0} and all(o % 256 == 0 for o in offset.values())
+        last = {}
+        for i, o in enumerate(ops):
+            last[o.inp] = i
+            if getattr(o, "res", None) is not None:
+                last[o.res] = i
+        last[ops[-1].out] = len(ops)
+        born = {o.out: i for i, o in enumerate(ops)}
+        lower = 0
+        for i, o in enumerate(ops):
+            alive = [t for t in offset if born[t] <= i <= last.get(t, born[t])]
+            assert o.out in alive and all(t in alive for t in (o.inp, getattr(o, "res", None)) if t)
+            spans = sorted((offset[t], offset[t] + nbytes[t]) for t in alive)
+            assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:])), f"overlap at op {i}"
+            assert spans[-1][1] <= top
+            lower = max(lower, sum(nbytes[t] for t in alive))
+        assert lower <= top <= sum(-(-b // 256) * 256 for t, b in nbytes.items() if t != 0)
+        assert W.memory_plan()["inference_arena"] == top
+    # ResNet-50: the arena reaches the lower bound (stem output + pooled output and the like), a sixth of all-kept
+    W = wl.Workload(4, "t", "bf16", 1, 224, 224, 3, wl.resnet50_ops(), np.zeros((1,), np.float32), train=False)
+    assert W.plan_inference_arena()[1] == 3612672 and W.memory_plan()["intermediates_all_kept"] == 22428672
