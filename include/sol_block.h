@@ -120,6 +120,38 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
  * descriptor is invalid: the pass itself then reports the error). */
 SOL_API size_t sol_block_workspace_bytes(const sol_block_desc* desc, int pass);
 
+/*
+ * Launch plans.  The paper tunes every layer on its own when a network is compiled (section "SOL
+ * architecture", the auto-tuning of the layer implementations).  Here the library picks tile
+ * shape, pipeline depth and the split of the weight gradient from the problem size, with thresholds
+ * measured over the benchmark network's layers; a caller may instead time the few candidates once
+ * per layer shape and install the winner.  A plan is looked up by the descriptor's shape, stride,
+ * padding and dtype (flags do not matter) and by the kernel it steers:
+ *   SOL_PLAN_FWD    forward GEMM:        tile, stages
+ *   SOL_PLAN_DGRAD  data-gradient GEMM:  tile, stages
+ *   SOL_PLAN_WGRAD  weight gradient:     splits (workgroups along N*Ho*Wo), stages
+ * tile: 0 = 128 pixels x 128 channels, 1 = 128 x 64, 2 = 64 x 64, 3 = 256 x 128 (stages 2 or 3
+ * only), -1 = library's choice.  stages: 2, 3 or 4 slices in flight, 0 = library's choice.
+ * splits: 0 = library's choice; the workspace size of the backward pass depends on it, so install
+ * plans before asking sol_block_workspace_bytes.  Plans only apply where the pipelined bf16 kernels
+ * run; elsewhere they are ignored.  They change speed, never which result is correct: forward and
+ * data gradient do not depend on the plan at all, the weight gradient only in the order of its fp32
+ * partial sums.  Host-only calls, safe from any thread (a small table behind a mutex).
+ */
+enum { SOL_PLAN_FWD = 0, SOL_PLAN_DGRAD = 1, SOL_PLAN_WGRAD = 2 };
+typedef struct {
+    int32_t tile;
+    int32_t stages;
+    int32_t splits;
+} sol_plan;
+/* Installs (plan != NULL) or removes (plan == NULL) the plan of one kernel of one layer shape.
+ * SOL_ERR_UNSUPPORTED for values outside the ranges above, SOL_ERR_SHAPE etc. for a bad descriptor. */
+SOL_API int sol_block_set_plan(const sol_block_desc* desc, int which, const sol_plan* plan);
+/* The installed plan, or {-1, 0, 0} when the library decides by itself. */
+SOL_API int sol_block_get_plan(const sol_block_desc* desc, int which, sol_plan* out);
+/* Removes every installed plan. */
+SOL_API void sol_clear_plans(void);
+
 /* Static, NUL-terminated description of a status code. */
 SOL_API const char* sol_status_string(int status);
 

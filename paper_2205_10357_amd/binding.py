@@ -14,10 +14,11 @@ from typing import Optional
 SOL_F32, SOL_BF16 = 0, 1
 SOL_RELU, SOL_DW_ACCUMULATE = 1, 2
 SOL_PASS_FWD, SOL_PASS_BWD = 0, 1
+SOL_PLAN_FWD, SOL_PLAN_DGRAD, SOL_PLAN_WGRAD = 0, 1, 2
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsol_block.so")
 EXPORTS = ("sol_block_fwd", "sol_block_bwd", "sol_block_workspace_bytes", "sol_status_string",
-           "sol_l1_loss_grad", "sol_maxpool_fwd")
+           "sol_l1_loss_grad", "sol_maxpool_fwd", "sol_block_set_plan", "sol_block_get_plan", "sol_clear_plans")
 
 _lib = None
 
@@ -32,6 +33,10 @@ class _CDesc(C.Structure):
     _fields_ = [("N", C.c_int32), ("H", C.c_int32), ("W", C.c_int32), ("C_in", C.c_int32),
                 ("C_out", C.c_int32), ("KH", C.c_int32), ("KW", C.c_int32),
                 ("stride", C.c_int32), ("pad", C.c_int32), ("dtype", C.c_int32), ("flags", C.c_uint32)]
+
+
+class _CPlan(C.Structure):
+    _fields_ = [("tile", C.c_int32), ("stages", C.c_int32), ("splits", C.c_int32)]
 
 
 @dataclass(frozen=True)
@@ -83,6 +88,12 @@ def lib():
         l.sol_l1_loss_grad.argtypes = [C.c_int32, vp, vp, vp, C.c_int64, C.c_int32, vp]
         l.sol_maxpool_fwd.restype = C.c_int
         l.sol_maxpool_fwd.argtypes = [C.c_int32, vp, vp] + [C.c_int32] * 7 + [vp]
+        l.sol_block_set_plan.restype = C.c_int
+        l.sol_block_set_plan.argtypes = [C.POINTER(_CDesc), C.c_int, C.POINTER(_CPlan)]
+        l.sol_block_get_plan.restype = C.c_int
+        l.sol_block_get_plan.argtypes = [C.POINTER(_CDesc), C.c_int, C.POINTER(_CPlan)]
+        l.sol_clear_plans.restype = None
+        l.sol_clear_plans.argtypes = []
         _lib = l
     return _lib
 
@@ -118,6 +129,31 @@ def _cdesc(desc) -> _CDesc:
 
 def sol_status_string(status: int) -> str:
     return lib().sol_status_string(int(status)).decode()
+
+
+def sol_block_set_plan(desc, which: int, plan: Optional[tuple], check: bool = True) -> int:
+    """plan: (tile, stages, splits) or None to remove the installed plan."""
+    d = _cdesc(desc)
+    if plan is None:
+        st = lib().sol_block_set_plan(C.byref(d), int(which), None)
+    else:
+        cp = _CPlan(int(plan[0]), int(plan[1]), int(plan[2]))
+        st = lib().sol_block_set_plan(C.byref(d), int(which), C.byref(cp))
+    if check and st != 0:
+        raise SolError(st, "sol_block_set_plan")
+    return st
+
+
+def sol_block_get_plan(desc, which: int) -> tuple:
+    d, cp = _cdesc(desc), _CPlan()
+    st = lib().sol_block_get_plan(C.byref(d), int(which), C.byref(cp))
+    if st != 0:
+        raise SolError(st, "sol_block_get_plan")
+    return (cp.tile, cp.stages, cp.splits)
+
+
+def sol_clear_plans() -> None:
+    lib().sol_clear_plans()
 
 
 def sol_block_workspace_bytes(desc, pass_: int) -> int:

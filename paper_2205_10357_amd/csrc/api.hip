@@ -3,6 +3,10 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
+#include <map>
+#include <mutex>
+
 #include "../../include/sol_block.h"
 #include "classes.h"
 #include "launch.h"
@@ -51,6 +55,26 @@ int env_int(const char* name, int fallback) {
     return atoi(v);
 }
 
+// ---- installed launch plans (sol_block_set_plan): shape -> tile / ring depth / split count ----
+struct PlanKey {
+    int32_t v[11];
+    bool operator<(const PlanKey& o) const { return memcmp(v, o.v, sizeof v) < 0; }
+};
+PlanKey plan_key(const sol_block_desc* d, int which) {
+    return PlanKey{{d->N, d->H, d->W, d->C_in, d->C_out, d->KH, d->KW, d->stride, d->pad, d->dtype, which}};
+}
+std::mutex g_plan_mutex;
+std::map<PlanKey, sol_plan> g_plans;
+std::atomic<int> g_plan_count{0};              // lets the common case (no plans) skip the lock
+sol_plan installed_plan(const sol_block_desc* d, int which) {
+    sol_plan out{-1, 0, 0};
+    if (g_plan_count.load(std::memory_order_acquire) == 0) return out;
+    std::lock_guard<std::mutex> lock(g_plan_mutex);
+    auto it = g_plans.find(plan_key(d, which));
+    if (it != g_plans.end()) out = it->second;
+    return out;
+}
+
 // Largest tile that still yields about one workgroup per compute unit; small problems fall
 // back to the smallest tile.  SOL_IGEMM_TILE overrides (tuning experiments).
 int pick_igemm_tile(const long long* class_rows, int ncls, int Nc) {
@@ -75,7 +99,7 @@ int pick_igemm_tile(const long long* class_rows, int ncls, int Nc) {
 // pipelined kernel (source channels % 64 == 0, output channels % 8 == 0, no mask on the gathered
 // operand) or the general one.  SOL_IGEMM_FAST=0 forces the general kernel; SOL_FAST_TILE /
 // SOL_FAST_STAGES override the pipelined kernel's tile and ring depth (tuning experiments).
-int run_igemm(IgemmParams& p, const long long* rows, bool mask, hipStream_t stream) {
+int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& tuned, hipStream_t stream) {
     bool few_taps = true;                       // the pipelined kernel keeps one validity bit per tap
     for (int c = 0; c < p.ncls; ++c) few_taps = few_taps && p.cls[c].Th * p.cls[c].Tw <= 32;
     const bool fast_ok = !mask && few_taps && (p.Cs % 64) == 0 && (p.Nc % 8) == 0 &&
@@ -89,6 +113,7 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, hipStream_t stre
             if (s > slices) slices = s;
         }
         tile = env_int("SOL_FAST_TILE", -1);
+        if (tile < 0 || tile > 3) tile = tuned.tile;              // an installed plan; the environment wins (experiments)
         if (tile < 0 || tile > 3) {
             // 128 x 128 unless that leaves most compute units idle or the GEMM is narrow
             long long t128 = 0;
@@ -110,6 +135,7 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, hipStream_t stre
             if (t < 160) tile = 2;
         }
         stages = env_int("SOL_FAST_STAGES", 0);
+        if (stages < 2 || stages > 4) stages = tuned.stages;
         if (stages < 2 || stages > 4) stages = (slices <= 4 || many_tiles) ? 2 : (slices <= 8 ? 3 : 4);
         if (tile == 3 && stages > 3) stages = 3;
         igemm_fast_tile_shape(tile, &bp, &bc);
@@ -160,8 +186,13 @@ BwdPlan plan_bwd(const sol_block_desc* d, const Geometry& g) {
         const long long tiles = (long long)b.tiles_k * b.tiles_c;
         const long long max_splits = (g.M + 127) / 128;
         long long want = env_int("SOL_WGRAD_SPLITS", 0);
+        if (want <= 0) want = installed_plan(d, SOL_PLAN_WGRAD).splits;
         if (want <= 0) {
-            const long long target = env_int("SOL_WGRAD_TARGET", 384);
+            // Workgroups aimed at (per-layer timing over the benchmark network's layers): the 1x1 / stride 1
+            // kernel runs three stages deep, one workgroup per compute unit, and is fastest with one wave of
+            // 256 workgroups; the gathering kernel runs two stages deep, two workgroups per compute unit: 512.
+            const bool linear = d->KH == 1 && d->KW == 1 && d->stride == 1 && d->pad == 0;
+            const long long target = env_int("SOL_WGRAD_TARGET", linear ? 256 : 512);
             want = (target + tiles - 1) / tiles;
             // keep the fp32 partials below ~64 MiB
             const long long cap = (64LL << 20) / (g.w_elems * 4 > 0 ? g.w_elems * 4 : 1);
@@ -253,7 +284,7 @@ int fwd_bf16(const sol_block_desc* d, const Geometry& g, const void* x, const vo
     c.tile_begin = 0;
     c.b_off = 0;
     const long long rows[1] = {g.M};
-    return run_igemm(p, rows, false, stream);
+    return run_igemm(p, rows, false, installed_plan(d, SOL_PLAN_FWD), stream);
 }
 
 int dgrad_bf16(const sol_block_desc* d, const Geometry& g, const void* dy, const void* y, const bf16_t* wpack,
@@ -322,7 +353,7 @@ int dgrad_bf16(const sol_block_desc* d, const Geometry& g, const void* dy, const
         launch_untouched_pixels(dx, addend, addend_mask, dx_mask, d->N, d->H, d->W, d->C_in, d->KH, d->KW, s, d->pad,
                                 stream) != hipSuccess)
         return SOL_ERR_LAUNCH;
-    return run_igemm(p, rows, relu, stream);
+    return run_igemm(p, rows, relu, installed_plan(d, SOL_PLAN_DGRAD), stream);
 }
 
 }  // namespace
@@ -475,8 +506,10 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
             const bool vec = bf16_vec;
             // pipelined kernel when dy needs no mask; SOL_WGRAD_FAST=0 forces the general kernel
             if (wgrad_pipelined) {
-                int stages = env_int("SOL_WGRAD_STAGES", 2);
-                if (stages < 2 || stages > 4) stages = 3;
+                int stages = env_int("SOL_WGRAD_STAGES", 0);
+                if (stages < 2 || stages > 4) stages = installed_plan(desc, SOL_PLAN_WGRAD).stages;
+                if (stages < 2 || stages > 4)
+                    stages = (desc->KH == 1 && desc->KW == 1 && desc->stride == 1 && desc->pad == 0) ? 3 : 2;
                 if (launch_wgrad_fast(wp, stages, st) != hipSuccess) return SOL_ERR_LAUNCH;
             } else if (launch_wgrad(wp, vec, relu, st) != hipSuccess) {
                 return SOL_ERR_LAUNCH;
@@ -508,6 +541,37 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
     }
     if (int e = data_branch(stream); e != SOL_OK) return e;
     return dW ? weight_branch(stream) : SOL_OK;
+}
+
+SOL_API int sol_block_set_plan(const sol_block_desc* desc, int which, const sol_plan* plan) {
+    if (!desc) return SOL_ERR_NULL;
+    if (which != SOL_PLAN_FWD && which != SOL_PLAN_DGRAD && which != SOL_PLAN_WGRAD) return SOL_ERR_UNSUPPORTED;
+    Geometry g;
+    if (int e = check_desc(desc, &g)) return e;
+    if (plan) {
+        const bool stages_ok = plan->stages == 0 || (plan->stages >= 2 && plan->stages <= 4);
+        if (!stages_ok || plan->tile < -1 || plan->tile > 3 || (plan->tile == 3 && plan->stages == 4) ||
+            plan->splits < 0 || plan->splits > 65535)
+            return SOL_ERR_UNSUPPORTED;
+    }
+    std::lock_guard<std::mutex> lock(g_plan_mutex);
+    if (plan) g_plans[plan_key(desc, which)] = *plan;
+    else g_plans.erase(plan_key(desc, which));
+    g_plan_count.store((int)g_plans.size(), std::memory_order_release);
+    return SOL_OK;
+}
+
+SOL_API int sol_block_get_plan(const sol_block_desc* desc, int which, sol_plan* out) {
+    if (!desc || !out) return SOL_ERR_NULL;
+    if (which != SOL_PLAN_FWD && which != SOL_PLAN_DGRAD && which != SOL_PLAN_WGRAD) return SOL_ERR_UNSUPPORTED;
+    *out = installed_plan(desc, which);
+    return SOL_OK;
+}
+
+SOL_API void sol_clear_plans(void) {
+    std::lock_guard<std::mutex> lock(g_plan_mutex);
+    g_plans.clear();
+    g_plan_count.store(0, std::memory_order_release);
 }
 
 SOL_API int sol_l1_loss_grad(int32_t dtype, const void* y, const void* t, void* dy, int64_t numel, int32_t mask_by_y,

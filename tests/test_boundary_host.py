@@ -18,7 +18,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = declared_symbols()
-    assert set(names) == set(B.EXPORTS) and len(names) == 6
+    assert set(names) == set(B.EXPORTS) and len(names) == 9
     lib = B.lib()
     for n in names:
         assert getattr(lib, n) is not None
@@ -106,3 +106,34 @@ def test_glue_validation():
     assert B.sol_l1_loss_grad(B.SOL_F32, None, FAKE, FAKE, 16, False, stream=0, check=False) == -1
     assert B.sol_maxpool_fwd(B.SOL_BF16, FAKE, FAKE, 1, 8, 8, 8, 3, 2, 3, stream=0, check=False) == -2
     assert B.sol_maxpool_fwd(B.SOL_BF16, FAKE, None, 1, 8, 8, 8, 3, 2, 1, stream=0, check=False) == -1
+
+
+def test_launch_plans_are_a_host_side_table():
+    """Install / read back / remove plans; value ranges; the backward workspace follows the split count."""
+    B.sol_clear_plans()
+    d = B.BlockDesc(64, 14, 14, 256, 256, 3, 3, 1, 1)
+    other = B.BlockDesc(64, 14, 14, 256, 256, 1, 1, 1, 0)
+    try:
+        assert B.sol_block_get_plan(d, B.SOL_PLAN_FWD) == (-1, 0, 0)
+        base = B.sol_block_workspace_bytes(d, B.SOL_PASS_BWD)
+        B.sol_block_set_plan(d, B.SOL_PLAN_FWD, (1, 3, 0))
+        B.sol_block_set_plan(d, B.SOL_PLAN_WGRAD, (-1, 3, 20))
+        assert B.sol_block_get_plan(d, B.SOL_PLAN_FWD) == (1, 3, 0)
+        assert B.sol_block_get_plan(d, B.SOL_PLAN_DGRAD) == (-1, 0, 0)              # per kernel
+        assert B.sol_block_get_plan(other, B.SOL_PLAN_FWD) == (-1, 0, 0)            # per shape
+        relu_off = B.BlockDesc(64, 14, 14, 256, 256, 3, 3, 1, 1, B.SOL_BF16, 0)
+        assert B.sol_block_get_plan(relu_off, B.SOL_PLAN_WGRAD) == (-1, 3, 20)      # flags do not matter
+        # 20 splits of 128-row granularity over 12544 rows, fp32 partial tiles of 2304 x 256
+        more = B.sol_block_workspace_bytes(d, B.SOL_PASS_BWD)
+        assert more > base and (more - base) % (2304 * 256 * 4) < 64 * 1024
+        for bad in ((4, 2, 0), (-2, 2, 0), (0, 1, 0), (0, 5, 0), (3, 4, 0), (0, 2, -1), (0, 2, 70000)):
+            assert B.sol_block_set_plan(d, B.SOL_PLAN_FWD, bad, check=False) == -4, bad
+        assert B.sol_block_set_plan(d, 3, (0, 2, 0), check=False) == -4
+        assert B.sol_block_set_plan(B.BlockDesc(0, 14, 14, 256, 256, 3, 3, 1, 1), 0, (0, 2, 0), check=False) == -2
+        assert B.sol_block_get_plan(d, B.SOL_PLAN_FWD) == (1, 3, 0)                 # failed calls change nothing
+        B.sol_block_set_plan(d, B.SOL_PLAN_WGRAD, None)
+        assert B.sol_block_workspace_bytes(d, B.SOL_PASS_BWD) == base
+        B.sol_clear_plans()
+        assert B.sol_block_get_plan(d, B.SOL_PLAN_FWD) == (-1, 0, 0)
+    finally:
+        B.sol_clear_plans()

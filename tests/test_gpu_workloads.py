@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 from oracle import oracle as orc                              # noqa: E402
-from paper_2205_10357_amd import runner, workloads as wl      # noqa: E402
+from paper_2205_10357_amd import binding as B, runner, tuning, workloads as wl      # noqa: E402
 from tests import parity_util as pu                           # noqa: E402
 
 TOL = 1e-2
@@ -304,3 +304,38 @@ def test_inference_arena_gives_the_retained_run_bit_for_bit(size):
         out = seq.forward()
         torch.cuda.synchronize()
         assert torch.equal(out, ref)
+
+
+def test_tuned_plans_change_speed_only():
+    """Time the candidate plans of the bottleneck's layers, install the winners (margin 0: whatever measured
+    fastest, so that plans really are in force), and run the step again: the forward output and the input
+    gradient keep their bits (they do not depend on tile shape or pipeline depth), the whole chain stays
+    within tolerance of the CPU checker, and clearing the table restores the weight gradient's bits."""
+    w = wl.bottleneck14_bf16(n=8)
+    last = w.ops[-1].out
+    try:
+        seq = runner.Sequencer(w, "cuda:0")
+        seq.step()
+        torch.cuda.synchronize()
+        y0, dx0 = seq.act[last].clone(), seq.dact[0].clone()
+        dw0 = {k: v["dW"].clone() for k, v in seq.grads.items()}
+        report = tuning.tune(seq, iters=3, margin=0.0)
+        assert set(report) == {"b.conv1", "b.conv2", "b.conv3"}
+        assert all(set(e) == {"fwd", "dgrad", "wgrad"} for e in report.values())
+        installed = [B.sol_block_get_plan(seq.desc[o.layer], k) for o in w.conv_blocks() for k in range(3)]
+        print("[tuning]", {n: {k: (v["plan"], round(v["default_ms"] * 1e3, 1), round(v["best_ms"] * 1e3, 1))
+                              for k, v in e.items()} for n, e in report.items()}, flush=True)
+        seq.step()
+        torch.cuda.synchronize()
+        assert torch.equal(seq.act[last], y0) and torch.equal(seq.dact[0], dx0)
+        for k, v in seq.grads.items():
+            assert rel(v["dW"].double().cpu().numpy(), dw0[k].double().cpu().numpy()) < 1e-5
+        if any(p != (-1, 0, 0) for p in installed):
+            check_chain_elementwise(w)                       # a fresh sequencer under the installed plans
+        B.sol_clear_plans()
+        seq2 = runner.Sequencer(w, "cuda:0")
+        seq2.step()
+        torch.cuda.synchronize()
+        assert all(torch.equal(seq2.grads[k]["dW"], dw0[k]) for k in dw0)
+    finally:
+        B.sol_clear_plans()
