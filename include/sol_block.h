@@ -117,7 +117,10 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
                   void* hip_stream);
 
 /* Bytes of caller-provided scratch the given pass needs for this descriptor (0 if the
- * descriptor is invalid: the pass itself then reports the error). */
+ * descriptor is invalid: the pass itself then reports the error).  The answer depends on every
+ * field of the descriptor, flags included (a backward pass that masks dy itself uses another
+ * weight-gradient kernel and another split than one that gets dy already masked): ask with the
+ * descriptor the call will carry. */
 SOL_API size_t sol_block_workspace_bytes(const sol_block_desc* desc, int pass);
 
 /*

@@ -111,10 +111,13 @@ class Sequencer:
             self.desc[o.layer] = d
             ws_bytes = max(ws_bytes, B.sol_block_workspace_bytes(d, B.SOL_PASS_FWD))
             if wl.train:
-                ws_bytes = max(ws_bytes, B.sol_block_workspace_bytes(d, B.SOL_PASS_BWD),
-                               B.sol_block_workspace_bytes(
-                                   B.BlockDesc(n, h, w, o.c_in, o.c_out, o.k, o.k, o.stride, o.pad,
-                                               self.sol_dtype, B.SOL_RELU), B.SOL_PASS_BWD))
+                # the backward calls carry the descriptor without SOL_RELU (gradients are stored masked);
+                # the answer depends on the flags, so ask for that one (and for the block's own, for callers
+                # that run a block's backward by hand)
+                for fl in (0, d.flags):
+                    ws_bytes = max(ws_bytes, B.sol_block_workspace_bytes(
+                        B.BlockDesc(n, h, w, o.c_in, o.c_out, o.k, o.k, o.stride, o.pad, self.sol_dtype, fl),
+                        B.SOL_PASS_BWD))
         self.ws = torch.empty((max(ws_bytes, 256),), dtype=torch.uint8, device=self.device)
         self._side: Optional[torch.cuda.Stream] = None
         self.grads: Dict[int, Dict[str, torch.Tensor]] = {}

@@ -83,7 +83,10 @@ def gpu_block(case, need_dx=True, want_dres=False, addend=None, addend_mask=None
         dW.copy_(torch.from_numpy(np.ascontiguousarray(np.transpose(dw_init, (0, 2, 3, 1)), np.float32)).cuda())
         dscale.fill_(1.0)
         dshift.fill_(-2.0)
-    ws_bytes = B.sol_block_workspace_bytes(desc, B.SOL_PASS_BWD)
+    # the backward call below may drop SOL_RELU (premasked): ask for the descriptor that call will carry
+    bwd_desc = B.BlockDesc(d.N, d.H, d.W, d.C_in, d.C_out, d.KH, d.KW, d.stride, d.pad, dt,
+                           flags & ~B.SOL_RELU) if premasked else desc
+    ws_bytes = B.sol_block_workspace_bytes(bwd_desc, B.SOL_PASS_BWD)
     ws = torch.full((ws_bytes // 4 + 64,), float("nan"), dtype=torch.float32, device="cuda")   # poisoned
     ad = to_dev(addend, bf16) if addend is not None else None
     am = to_dev(addend_mask, bf16) if addend_mask is not None else None
