@@ -306,6 +306,27 @@ def test_inference_arena_gives_the_retained_run_bit_for_bit(size):
         assert torch.equal(out, ref)
 
 
+def test_plan_sweep_covers_strided_and_projection_layers():
+    """The sweep on the stage-2 topology (stride-2 3x3, stride-2 1x1 projection, identity blocks): every distinct
+    layer shape is timed for the kernels that serve it, installed plans are valid table entries, and the chain
+    still matches the CPU checker under them."""
+    w = wl.stage2_train_bf16(n=2, faithful=True, hw=28)
+    try:
+        seq = runner.Sequencer(w, "cuda:0")
+        seq.step()
+        report = tuning.tune(seq, iters=3, margin=0.0)
+        shapes = {(o.c_in, o.c_out, o.k, o.stride, seq.shapes[o.inp][1]) for o in w.conv_blocks()}
+        assert len(report) == len(shapes)
+        for name, e in report.items():
+            assert "fwd" in e and "wgrad" in e, name
+            for kind, v in e.items():
+                assert v["best_ms"] <= v["default_ms"] and (v["plan"] is None or len(v["plan"]) == 3), (name, kind)
+        del seq
+        check_chain_elementwise(w)
+    finally:
+        B.sol_clear_plans()
+
+
 def test_tuned_plans_change_speed_only():
     """Time the candidate plans of the bottleneck's layers, install the winners (margin 0: whatever measured
     fastest, so that plans really are in force), and run the step again: the forward output and the input
