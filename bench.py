@@ -103,7 +103,7 @@ def workloads_bytes(n, shp, b):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py measures one GPU only (this build has no multi-GPU path); run with --gpus 1",
+        print("bench.py measures one GPU only (the library has no multi-GPU path); run with --gpus 1",
               file=sys.stderr)
         sys.exit(2)
     import torch
