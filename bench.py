@@ -52,7 +52,9 @@ def parse():
     ap.add_argument("--tune", action="store_true",
                     help="before the warm-up, time the candidate launch plans of every layer shape and install the "
                          "winners (seconds; outside the timed region)")
-    ap.add_argument("--cpu-sample-images", type=int, default=32)
+    ap.add_argument("--cpu-sample-images", type=int, default=0,
+                    help="images the CPU checker is timed on (0 = per workload: the whole batch of the stem and the "
+                         "bottleneck, 8 images of the ResNet-50 and stage-2 schedules: 5 to 30 s)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run three plain device copies of 256 MiB (torch's copy kernel): under a counter "
                          "profile their FETCH_SIZE / WRITE_SIZE readings give the scale of those counters")
@@ -67,15 +69,18 @@ def cpu_baseline(wl_factory, images: int):
     shp = wl.tensor_shapes()
     t0 = time.perf_counter()
     acts = {0: wl.x.astype(np.float64)}
-    for o in wl.conv_blocks():
+    for o in wl.ops:
+        if o.op != "conv":
+            acts[o.out] = orc.maxpool(acts[o.inp], o.k, o.stride, o.pad)
+            continue
         p = wl.params[o.layer]
         _, h, w = shp[o.inp]
         d = orc.Desc(wl.n, h, w, o.c_in, o.c_out, o.k, o.k, o.stride, o.pad, o.relu)
         acts[o.out] = orc.block_fwd(d, acts[o.inp], p["W"], p["scale"], p["shift"],
                                     acts[o.res] if o.res is not None else None)
     last = wl.conv_blocks()[-1].out
-    grads = {last: orc.l1_grad(acts[last], wl.target)}
-    for o in reversed(wl.conv_blocks()):
+    grads = {last: orc.l1_grad(acts[last], wl.target)} if wl.train else {}
+    for o in reversed(wl.conv_blocks() if wl.train else []):
         p = wl.params[o.layer]
         _, h, w = shp[o.inp]
         d = orc.Desc(wl.n, h, w, o.c_in, o.c_out, o.k, o.k, o.stride, o.pad, o.relu)
@@ -203,10 +208,11 @@ def main():
                      "kernel": "igemm_fast_kernel", "launch": f"{big.name} forward", "avg_us": round(k_us, 3)},
     }
     if not args.no_cpu_baseline:
-        images = min(args.cpu_sample_images, n)
+        images = min(args.cpu_sample_images or {2: 32, 3: 64, 4: 8, 5: 8}[args.workload], n)
         v, secs, cores = cpu_baseline(factories[args.workload], images)
         out["cpu_baseline"] = {"value": round(v, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-                               "sample": f"first {images} of {n} images, forward + L1 gradient + backward, "
+                               "sample": f"first {images} of {n} images, " +
+                                         ("forward + L1 gradient + backward, " if wl.train else "forward, ") +
                                          f"{secs:.1f} s"}
     print(json.dumps(out))
 
