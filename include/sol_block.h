@@ -93,9 +93,12 @@ SOL_API int sol_block_fwd(const sol_block_desc* desc, const void* x, const void*
  * Nullable: dx (skips the data gradient altogether), dres, dx_addend, dx_addend_mask, dx_mask;
  * dW, dscale and dshift may be NULL together (skips the weight branch: the split weight-gradient
  * GEMM and its reduction); at least one of dx, dres, dW must be given.  The data branch and the
- * weight branch read the same inputs and use disjoint parts of the workspace, so a caller may
- * issue them as two calls on two streams (one with dW = NULL, one with dx = dres = NULL), sharing
- * one workspace, as long as calls of the same kind are ordered among themselves.
+ * weight branch of ONE block read the same inputs and use disjoint parts of the workspace, so a
+ * caller may issue them as two calls on two streams (one with dW = NULL, one with dx = dres =
+ * NULL) sharing one workspace.  That holds for two calls with the same descriptor only: where the
+ * parts lie depends on the descriptor, so calls for different blocks that may overlap in time
+ * (a weight branch still running on a side stream while the next block starts) need a workspace
+ * each.
  *   dres            out, [N][Ho][Wo][C_out]: g itself (the gradient of the residual input).
  *   dx_addend       in,  [N][H][W][C_in]: added to dx in the epilogue (shortcut gradients).
  *   dx_addend_mask  in,  same shape as dx_addend: when given, only elements whose mask value
@@ -154,6 +157,12 @@ SOL_API int sol_block_set_plan(const sol_block_desc* desc, int which, const sol_
 SOL_API int sol_block_get_plan(const sol_block_desc* desc, int which, sol_plan* out);
 /* Removes every installed plan. */
 SOL_API void sol_clear_plans(void);
+
+/* Tuning-experiment overrides (environment variables SOL_IGEMM_FAST, SOL_FAST_TILE, SOL_FAST_STAGES,
+ * SOL_IGEMM_TILE, SOL_WGRAD_FAST, SOL_WGRAD_SPLITS, SOL_WGRAD_STAGES, ...: they win over installed
+ * plans) are read once, by the first call that looks at one, not per call.  This reads them again;
+ * for tests and sweeps that change the environment of a running process.  Host-only. */
+SOL_API void sol_reload_overrides(void);
 
 /* Static, NUL-terminated description of a status code. */
 SOL_API const char* sol_status_string(int status);

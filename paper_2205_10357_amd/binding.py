@@ -18,7 +18,8 @@ SOL_PLAN_FWD, SOL_PLAN_DGRAD, SOL_PLAN_WGRAD = 0, 1, 2
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsol_block.so")
 EXPORTS = ("sol_block_fwd", "sol_block_bwd", "sol_block_workspace_bytes", "sol_status_string",
-           "sol_l1_loss_grad", "sol_maxpool_fwd", "sol_block_set_plan", "sol_block_get_plan", "sol_clear_plans")
+           "sol_l1_loss_grad", "sol_maxpool_fwd", "sol_block_set_plan", "sol_block_get_plan", "sol_clear_plans",
+           "sol_reload_overrides")
 
 _lib = None
 
@@ -94,6 +95,8 @@ def lib():
         l.sol_block_get_plan.argtypes = [C.POINTER(_CDesc), C.c_int, C.POINTER(_CPlan)]
         l.sol_clear_plans.restype = None
         l.sol_clear_plans.argtypes = []
+        l.sol_reload_overrides.restype = None
+        l.sol_reload_overrides.argtypes = []
         _lib = l
     return _lib
 
@@ -154,6 +157,10 @@ def sol_block_get_plan(desc, which: int) -> tuple:
 
 def sol_clear_plans() -> None:
     lib().sol_clear_plans()
+
+
+def sol_reload_overrides() -> None:
+    lib().sol_reload_overrides()
 
 
 def sol_block_workspace_bytes(desc, pass_: int) -> int:

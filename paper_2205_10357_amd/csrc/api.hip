@@ -1,5 +1,6 @@
 // C-ABI of the fused block: argument validation (host only, before any HIP call), launch
 // planning (tile shape, split count, workspace layout) and the calls into the kernels.
+#include <limits.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -49,10 +50,33 @@ int check_desc(const sol_block_desc* d, Geometry* g) {
 // framework included); drop it so that the check after our launches sees only our own.
 inline void clear_stale_error() { (void)hipGetLastError(); }
 
-int env_int(const char* name, int fallback) {
-    const char* v = getenv(name);
-    if (!v || !*v) return fallback;
-    return atoi(v);
+// Tuning-experiment overrides from the environment.  They are read once (at the first call that needs one,
+// or when sol_reload_overrides() asks for it), never per call: every getenv walks the whole environment, and a
+// backward call used to make some fifteen of them.
+enum Knob {
+    K_IGEMM_TILE, K_IGEMM_FAST, K_FAST_TILE, K_FAST_SHORTK, K_FAST_MANY, K_FAST_STAGES, K_WGRAD_SPLITS, K_WGRAD_TARGET,
+    K_SMALLC, K_FILL_UNTOUCHED, K_WGRAD_FAST, K_PACK_FUSED, K_WGRAD_STAGES, K_WGRAD_TICKET, K_COUNT
+};
+const char* const kKnobNames[K_COUNT] = {
+    "SOL_IGEMM_TILE", "SOL_IGEMM_FAST", "SOL_FAST_TILE", "SOL_FAST_SHORTK", "SOL_FAST_MANY", "SOL_FAST_STAGES",
+    "SOL_WGRAD_SPLITS", "SOL_WGRAD_TARGET", "SOL_SMALLC", "SOL_FILL_UNTOUCHED", "SOL_WGRAD_FAST", "SOL_PACK_FUSED",
+    "SOL_WGRAD_STAGES", "SOL_WGRAD_TICKET"};
+constexpr int kKnobUnset = INT32_MIN;
+std::atomic<int> g_knobs[K_COUNT];
+std::atomic<bool> g_knobs_loaded{false};
+std::mutex g_knob_mutex;
+void load_knobs() {
+    std::lock_guard<std::mutex> lock(g_knob_mutex);
+    for (int k = 0; k < K_COUNT; ++k) {
+        const char* v = getenv(kKnobNames[k]);
+        g_knobs[k].store(v && *v ? atoi(v) : kKnobUnset, std::memory_order_relaxed);
+    }
+    g_knobs_loaded.store(true, std::memory_order_release);
+}
+int knob(Knob k, int fallback) {
+    if (!g_knobs_loaded.load(std::memory_order_acquire)) load_knobs();
+    const int v = g_knobs[k].load(std::memory_order_relaxed);
+    return v == kKnobUnset ? fallback : v;
 }
 
 // ---- installed launch plans (sol_block_set_plan): shape -> tile / ring depth / split count ----
@@ -78,7 +102,7 @@ sol_plan installed_plan(const sol_block_desc* d, int which) {
 // Largest tile that still yields about one workgroup per compute unit; small problems fall
 // back to the smallest tile.  SOL_IGEMM_TILE overrides (tuning experiments).
 int pick_igemm_tile(const long long* class_rows, int ncls, int Nc) {
-    const int forced = env_int("SOL_IGEMM_TILE", -1);
+    const int forced = knob(K_IGEMM_TILE, -1);
     if (forced >= 0 && forced <= 3) return forced;
     const int order_wide[4] = {1, 0, 2, 3};
     const int order_narrow[2] = {2, 3};
@@ -103,7 +127,7 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& 
     bool few_taps = true;                       // the pipelined kernel keeps one validity bit per tap
     for (int c = 0; c < p.ncls; ++c) few_taps = few_taps && p.cls[c].Th * p.cls[c].Tw <= 32;
     const bool fast_ok = !mask && few_taps && (p.Cs % 64) == 0 && (p.Nc % 8) == 0 &&
-                         env_int("SOL_IGEMM_FAST", 1) != 0;
+                         knob(K_IGEMM_FAST, 1) != 0;
     int bp, bc, tile = 0, stages = 0;
     bool many_tiles = false;
     if (fast_ok) {
@@ -112,7 +136,7 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& 
             const long long s = (long long)p.cls[c].Th * p.cls[c].Tw * (p.Cs / 64);
             if (s > slices) slices = s;
         }
-        tile = env_int("SOL_FAST_TILE", -1);
+        tile = knob(K_FAST_TILE, -1);
         if (tile < 0 || tile > 3) tile = tuned.tile;              // an installed plan; the environment wins (experiments)
         if (tile < 0 || tile > 3) {
             // 128 x 128 unless that leaves most compute units idle or the GEMM is narrow
@@ -122,11 +146,11 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& 
             tile = p.Nc <= 64 ? 1 : (t128 >= 160 ? 0 : 1);
             // short reductions are dominated by per-workgroup latency (prologue, epilogue): many small
             // workgroups per compute unit hide it better than few large ones
-            if (slices <= env_int("SOL_FAST_SHORTK", 4) && t128 >= 512) tile = 2;
+            if (slices <= knob(K_FAST_SHORTK, 4) && t128 >= 512) tile = 2;
             // many tiles per compute unit: 128 x 64 tiles with two stages leave room for three workgroups per
             // compute unit, whose prologues and epilogues overlap (measured over the ResNet-50 layer shapes:
             // best or within a few percent of best from ~3 tiles of 128 x 128 per compute unit upwards)
-            many_tiles = t128 >= env_int("SOL_FAST_MANY", 700) * (slices <= 4 ? 2 : 1);   // short reductions: 64 x 64 holds up longer
+            many_tiles = t128 >= knob(K_FAST_MANY, 700) * (slices <= 4 ? 2 : 1);   // short reductions: 64 x 64 holds up longer
             if (many_tiles) tile = 1;
             long long t = 0;
             igemm_fast_tile_shape(tile, &bp, &bc);
@@ -134,7 +158,7 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& 
             t *= (p.Nc + bc - 1) / bc;
             if (t < 160) tile = 2;
         }
-        stages = env_int("SOL_FAST_STAGES", 0);
+        stages = knob(K_FAST_STAGES, 0);
         if (stages < 2 || stages > 4) stages = tuned.stages;
         if (stages < 2 || stages > 4) stages = (slices <= 4 || many_tiles) ? 2 : (slices <= 8 ? 3 : 4);
         if (tile == 3 && stages > 3) stages = 3;
@@ -185,14 +209,14 @@ BwdPlan plan_bwd(const sol_block_desc* d, const Geometry& g) {
         b.tiles_c = (d->C_out + 127) / 128;
         const long long tiles = (long long)b.tiles_k * b.tiles_c;
         const long long max_splits = (g.M + 127) / 128;
-        long long want = env_int("SOL_WGRAD_SPLITS", 0);
+        long long want = knob(K_WGRAD_SPLITS, 0);
         if (want <= 0) want = installed_plan(d, SOL_PLAN_WGRAD).splits;
         if (want <= 0) {
             // Workgroups aimed at (per-layer timing over the benchmark network's layers): the 1x1 / stride 1
             // kernel runs three stages deep, one workgroup per compute unit, and is fastest with one wave of
             // 256 workgroups; the gathering kernel runs two stages deep, two workgroups per compute unit: 512.
             const bool linear = d->KH == 1 && d->KW == 1 && d->stride == 1 && d->pad == 0;
-            const long long target = env_int("SOL_WGRAD_TARGET", linear ? 256 : 512);
+            const long long target = knob(K_WGRAD_TARGET, linear ? 256 : 512);
             want = (target + tiles - 1) / tiles;
             // keep the fp32 partials below ~64 MiB
             const long long cap = (64LL << 20) / (g.w_elems * 4 > 0 ? g.w_elems * 4 : 1);
@@ -210,7 +234,7 @@ BwdPlan plan_bwd(const sol_block_desc* d, const Geometry& g) {
     b.dshift_off = b.part_off + align_up((size_t)b.splits * g.w_elems * 4);
     b.total = b.dshift_off + align_up((size_t)b.splits * d->C_out * 4);
     b.smallc = d->dtype == SOL_BF16 && smallc_wgrad_supported(d->C_in, d->C_out, d->KH, d->KW, d->stride) &&
-               env_int("SOL_SMALLC", 1) != 0;
+               knob(K_SMALLC, 1) != 0;
     if (b.smallc) {
         b.sc_parts = smallc_wgrad_parts(d->N, g.Ho, g.Wo);
         b.sc_xp_off = b.total;
@@ -228,7 +252,7 @@ struct FwdPlan {
 FwdPlan plan_fwd(const sol_block_desc* d) {
     FwdPlan f{};
     f.smallc = d->dtype == SOL_BF16 && smallc_fwd_supported(d->C_in, d->C_out, d->KH, d->KW, d->stride) &&
-               env_int("SOL_SMALLC", 1) != 0;
+               knob(K_SMALLC, 1) != 0;
     if (f.smallc) {
         f.xp_off = 0;
         f.wp_off = align_up(smallc_padded_image_bytes(d->N, d->H, d->W));
@@ -313,7 +337,7 @@ int dgrad_bf16(const sol_block_desc* d, const Geometry& g, const void* dy, const
     int nc = 0;
     // pixels without a tap (1x1 / stride 2: three quarters of dx) are filled at memory speed by a launch of their
     // own; as GEMM tiles without a reduction they cost several times that
-    const bool fill_untouched = (d->C_in % 8) == 0 && env_int("SOL_FILL_UNTOUCHED", 1) != 0;
+    const bool fill_untouched = (d->C_in % 8) == 0 && knob(K_FILL_UNTOUCHED, 1) != 0;
     bool any_untouched = false;
     for (int ph = 0; ph < s; ++ph)
         for (int pw = 0; pw < s; ++pw) {
@@ -410,9 +434,10 @@ SOL_API int sol_block_fwd(const sol_block_desc* desc, const void* x, const void*
     return launch_direct_fwd_f32(p, stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
 }
 
-SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void* x, const void* W, const void* y, void* dx,
-                  float* dW, float* dscale, float* dshift, const float* scale, void* dres, const void* dx_addend,
-                  const void* dx_addend_mask, const void* dx_mask, void* ws, size_t ws_bytes, void* hip_stream) {
+static int bwd_common(const sol_block_desc* desc, const void* dy, const void* x, const void* W, const void* y, void* dx,
+                      float* dW, float* dscale, float* dshift, const float* scale, void* dres, const void* dx_addend,
+                      const void* dx_addend_mask, const void* dx_mask, void* ws, size_t ws_bytes, bool builtin_scratch,
+                      void* hip_stream) {
     Geometry g;
     if (int e = check_desc(desc, &g); e != SOL_OK) return e;
     const bool relu = (desc->flags & SOL_RELU) != 0;
@@ -457,10 +482,10 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
     // The re-pack of the weights for the data gradient rides along with the weight-gradient launch (as extra
     // workgroups) when one call computes both branches with the pipelined kernels; else it is a launch of its own.
     const bool bf16_vec = desc->dtype == SOL_BF16 && (desc->C_in % 8) == 0 && (desc->C_out % 8) == 0;
-    const bool wgrad_pipelined = bf16_vec && !relu && env_int("SOL_WGRAD_FAST", 1) != 0;
+    const bool wgrad_pipelined = bf16_vec && !relu && knob(K_WGRAD_FAST, 1) != 0;
     PackParams pk{(const bf16_t*)W, scale, (bf16_t*)(wsb + plan.wpack_off), desc->C_in, desc->C_out, desc->KH,
                   desc->KW, desc->stride, desc->pad};
-    const bool pack_rides = dx && dW && wgrad_pipelined && pack_tiled_ok(pk) && env_int("SOL_PACK_FUSED", 1) != 0;
+    const bool pack_rides = dx && dW && wgrad_pipelined && pack_tiled_ok(pk) && knob(K_PACK_FUSED, 1) != 0;
 
     // ---- data branch: shortcut gradient, weight re-pack, data-gradient GEMM ----
     auto data_branch = [&](hipStream_t st) -> int {
@@ -506,7 +531,7 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
             const bool vec = bf16_vec;
             // pipelined kernel when dy needs no mask; SOL_WGRAD_FAST=0 forces the general kernel
             if (wgrad_pipelined) {
-                int stages = env_int("SOL_WGRAD_STAGES", 0);
+                int stages = knob(K_WGRAD_STAGES, 0);
                 if (stages < 2 || stages > 4) stages = installed_plan(desc, SOL_PLAN_WGRAD).stages;
                 if (stages < 2 || stages > 4)
                     stages = (desc->KH == 1 && desc->KW == 1 && desc->stride == 1 && desc->pad == 0) ? 3 : 2;
@@ -543,6 +568,13 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
     return dW ? weight_branch(stream) : SOL_OK;
 }
 
+SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void* x, const void* W, const void* y, void* dx,
+                  float* dW, float* dscale, float* dshift, const float* scale, void* dres, const void* dx_addend,
+                  const void* dx_addend_mask, const void* dx_mask, void* ws, size_t ws_bytes, void* hip_stream) {
+    return bwd_common(desc, dy, x, W, y, dx, dW, dscale, dshift, scale, dres, dx_addend, dx_addend_mask, dx_mask, ws,
+                      ws_bytes, false, hip_stream);
+}
+
 SOL_API int sol_block_set_plan(const sol_block_desc* desc, int which, const sol_plan* plan) {
     if (!desc) return SOL_ERR_NULL;
     if (which != SOL_PLAN_FWD && which != SOL_PLAN_DGRAD && which != SOL_PLAN_WGRAD) return SOL_ERR_UNSUPPORTED;
@@ -567,6 +599,8 @@ SOL_API int sol_block_get_plan(const sol_block_desc* desc, int which, sol_plan* 
     *out = installed_plan(desc, which);
     return SOL_OK;
 }
+
+SOL_API void sol_reload_overrides(void) { load_knobs(); }
 
 SOL_API void sol_clear_plans(void) {
     std::lock_guard<std::mutex> lock(g_plan_mutex);

@@ -101,6 +101,16 @@ __device__ __forceinline__ void wg_barrier() {
     asm volatile("" ::"s"(a), "s"(b), "s"(c), "s"(d), "s"(e), "s"(f), "s"(g), "s"(h))
 #endif
 
+// Workgroup ids are dealt round-robin to the 8 XCDs (each with an L2 of its own); this gives every XCD a
+// contiguous range of logical tile indices, so that tiles sharing activation rows or a weight panel also
+// share an L2.  nblocks = workgroups of the launch that take part.
+__device__ __forceinline__ int xcd_remap(int bid, int nblocks) {
+    const int per = nblocks >> 3, rem = nblocks & 7;
+    const int xcd = bid & 7, idx = bid >> 3;
+    const int start = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
+    return start + idx;
+}
+
 // ---- division by a launch-invariant divisor (n < 2^31): q = (mulhi(n, magic) + n) >> shift ------
 struct FastDiv {
     uint32_t magic, shift;

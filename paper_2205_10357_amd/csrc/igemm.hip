@@ -18,15 +18,6 @@ namespace sol {
 
 __device__ __forceinline__ int lds_swizzle(int row) { return (row + (row >> 3)) & 7; }
 
-// Workgroup ids are dealt round-robin to the 8 XCDs; give every XCD a contiguous range of
-// logical tiles so that tiles sharing activation rows also share that XCD's L2.
-__device__ __forceinline__ int xcd_remap(int bid, int nblocks) {
-    const int per = nblocks >> 3, rem = nblocks & 7;
-    const int xcd = bid & 7, idx = bid >> 3;
-    const int start = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
-    return start + idx;
-}
-
 template <int BP, int BC, int WP, int WC, bool VEC, bool MASK>
 __global__ __launch_bounds__(256) void igemm_bf16_kernel(const IgemmParams p) {
     static_assert(WP * WC == 4, "four waves per workgroup");

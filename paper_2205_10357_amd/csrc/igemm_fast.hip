@@ -20,13 +20,6 @@ namespace sol {
 
 __device__ __forceinline__ int fast_swizzle(int row) { return (row + (row >> 3)) & 7; }
 
-__device__ __forceinline__ int fast_xcd_remap(int bid, int nblocks) {
-    const int per = nblocks >> 3, rem = nblocks & 7;
-    const int xcd = bid & 7, idx = bid >> 3;
-    const int start = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
-    return start + idx;
-}
-
 // Pins "NC async copies and NM MFMAs" as copy, MFMA, copy, MFMA, ...: a copy holds the wave's issue
 // port for some twenty cycles, which one MFMA in flight covers and two copies in a row do not.
 template <int NC, int NM>
@@ -65,7 +58,7 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
     SOL_FETCH_NOW_8(rc.w_off, rc.Th, rc.Tw, rc.tap_step, rc.oh_mul, rc.oh_off, rc.ow_mul, rc.ow_off);
     SOL_FETCH_NOW_8(rc.tile_begin, rc.linear, rc.b_off, rc.div_img.magic, rc.div_img.shift, rc.div_rw.magic,
                     rc.div_rw.shift, p.total_tiles);
-    const int bid = fast_xcd_remap(blockIdx.x, p.total_tiles);     // the launch has total_tiles workgroups
+    const int bid = xcd_remap(blockIdx.x, p.total_tiles);     // the launch has total_tiles workgroups
     const int tc = bid % p.tiles_c;
     int tp = bid / p.tiles_c;
     if (p.ncls > 1) {

@@ -205,8 +205,7 @@ template <int KH>
 static hipError_t launch_smallc_fwd_kh(const SmallCParams& p, hipStream_t stream) {
     const int segs = (p.Wo + SC_TILE - 1) / SC_TILE;
     const long long tiles = (long long)p.N * p.Ho * segs;
-    const char* gv = getenv("SOL_SMALLC_GRID");
-    const long long cap = gv && *gv ? atoi(gv) : 512;          // two workgroups per compute unit
+    const long long cap = 512;                                 // two workgroups per compute unit
     const int grid = (int)(tiles < cap ? tiles : cap);         // several tiles per workgroup amortise the weight fetch
     hipLaunchKernelGGL(smallc_fwd_kernel<KH>, dim3(grid), dim3(256), 0, stream, p);
     return hipGetLastError();

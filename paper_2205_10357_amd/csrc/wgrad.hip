@@ -16,13 +16,6 @@
 
 namespace sol {
 
-__device__ __forceinline__ int xcd_remap_w(int bid, int nblocks) {
-    const int per = nblocks >> 3, rem = nblocks & 7;
-    const int xcd = bid & 7, idx = bid >> 3;
-    const int start = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
-    return start + idx;
-}
-
 // rows r[0..7] hold 8 consecutive channels of 8 consecutive m; on return o[j] holds the 8
 // consecutive m of channel j (16-bit elements).
 __device__ __forceinline__ void transpose8x8_b16(const uintx4 (&r)[8], uintx4 (&o)[8]) {
@@ -50,7 +43,7 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(const WgradParams p) {
     HIP_DYNAMIC_SHARED(uintx4, lds)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int bid = xcd_remap_w(blockIdx.x, gridDim.x);
+    const int bid = xcd_remap(blockIdx.x, gridDim.x);
     const int tiles = p.tiles_k * p.tiles_c;
     const int split = bid / tiles;
     const int t = bid - split * tiles;

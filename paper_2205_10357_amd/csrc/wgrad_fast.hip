@@ -23,13 +23,6 @@
 
 namespace sol {
 
-__device__ __forceinline__ int wgf_xcd_remap(int bid, int nblocks) {
-    const int per = nblocks >> 3, rem = nblocks & 7;
-    const int xcd = bid & 7, idx = bid >> 3;
-    const int start = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
-    return start + idx;
-}
-
 constexpr int WGF_TILE = 128;                 // tile edge along k and along co
 constexpr int WGF_BM = 64;                    // reduction rows per slice
 constexpr int WGF_OPER = WGF_BM * 16;         // 16-byte chunks of one operand tile
@@ -52,7 +45,7 @@ __global__ __launch_bounds__(256) void wgrad_fast_kernel(const WgradParams p) {
         pack_dgrad_weights_tile(p.pack, (int)blockIdx.x - nwg, reinterpret_cast<bf16_t*>(lds));
         return;
     }
-    const int bid = wgf_xcd_remap(blockIdx.x, nwg);
+    const int bid = xcd_remap(blockIdx.x, nwg);
     const int split = bid / tiles;
     const int t = bid - split * tiles;
     const int tk = t % p.tiles_k, tcn = t / p.tiles_k;

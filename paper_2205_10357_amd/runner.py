@@ -21,8 +21,12 @@ block's dy); a block's weight branch (weight gradient, its reduction, dscale, ds
 needs nothing but that block's dy and x.  At ResNet sizes neither kind of kernel fills the chip
 (a data-gradient GEMM has fewer tiles than there are compute units), so ``backward(lanes=2)``
 issues the weight branches on a second stream that waits, block by block, for the gradient they
-read, and joins the first stream at the end of the step (a few percent faster than one lane,
-measured; a captured graph runs its branches no faster than one lane).
+read, and joins the first stream at the end of the step.  The second lane has a workspace of its
+own: where a call keeps its packed weights and its split partials inside the workspace depends on
+the block's shape, and the weight branch of one block is still running when the data branch of
+the next one starts.  Measured, two lanes are no faster than one (the large kernels of both lanes
+each want the whole chip, and a captured graph runs its branches no faster than one stream), so
+one lane is the default.
 """
 from __future__ import annotations
 
@@ -120,6 +124,7 @@ class Sequencer:
                         B.SOL_PASS_BWD))
         self.ws = torch.empty((max(ws_bytes, 256),), dtype=torch.uint8, device=self.device)
         self._side: Optional[torch.cuda.Stream] = None
+        self._ws_side: Optional[torch.Tensor] = None      # workspace of the second backward lane
         self.grads: Dict[int, Dict[str, torch.Tensor]] = {}
         self.dact: Dict[int, torch.Tensor] = {}
         self.target: Optional[torch.Tensor] = None
@@ -228,6 +233,7 @@ class Sequencer:
         main = stream if stream is not None else torch.cuda.current_stream(self.device)
         if self._side is None:
             self._side = torch.cuda.Stream(device=self.device)       # default priority
+            self._ws_side = torch.empty_like(self.ws)
         side = self._side
         for c in self._bwd_calls:
             o = c["op"]
@@ -235,7 +241,7 @@ class Sequencer:
             # dy of this block is complete on the main lane here (loss kernel or the previous data gradient)
             side.wait_stream(main)
             B.sol_block_bwd(c["desc"], c["dy"], self.act[o.inp], p["W"], None, None, g["dW"], g["dscale"],
-                            g["dshift"], p["scale"], None, None, None, None, self.ws, None, side)
+                            g["dshift"], p["scale"], None, None, None, None, self._ws_side, None, side)
             if c["dx"] is not None:
                 B.sol_block_bwd(c["desc"], c["dy"], self.act[o.inp], p["W"], None, c["dx"], None, None, None,
                                 p["scale"], None, c["addend"], None, c["dx_mask"], self.ws, None, main)
@@ -260,6 +266,8 @@ class Sequencer:
 
     def step(self, stream=None, lanes: int = 1) -> None:
         """One pass of the whole path: forward, and for training the loss gradient and backward."""
+        if stream is None:
+            stream = torch.cuda.current_stream(self.device)     # looked up once per step, not once per call
         self.forward(stream)
         if self.wl.train:
             self.loss_grad(stream)

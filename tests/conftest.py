@@ -27,3 +27,18 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+@pytest.fixture
+def sol_env(monkeypatch):
+    """Set a tuning override of the library for one test: the library reads its environment overrides once,
+    so it is told to read them again after every change and after the test."""
+    from paper_2205_10357_amd import binding as B
+
+    def set_override(name, value):
+        monkeypatch.setenv(name, str(value))
+        B.sol_reload_overrides()
+
+    yield set_override
+    monkeypatch.undo()
+    B.sol_reload_overrides()

@@ -11,6 +11,27 @@ from paper_2205_10357_amd import binding as B
 from paper_2205_10357_amd import workloads as wl
 
 TOL = {"f32": 1e-5, "bf16": 1e-2}   # max relative L2 error per output tensor
+# dW, dscale and dshift are float32 in both modes: float32 sums of products that are exact in float32
+# (bf16 x bf16), so they are held to the float32 tolerance whatever the storage type of the activations
+TOL_F32_OUTPUTS = 1e-5
+
+
+def bf16_ulp(ref: np.ndarray) -> np.ndarray:
+    """Spacing of the bf16 grid at |ref| (8 significand bits; the smallest normal exponent below that)."""
+    a = np.maximum(np.abs(np.asarray(ref, np.float64)), 2.0 ** -126)
+    return 2.0 ** (np.floor(np.log2(a)) - 7)
+
+
+def assert_elementwise_bf16(name: str, got: np.ndarray, ref: np.ndarray, mag: np.ndarray) -> None:
+    """Every element, not only the norm: a stored bf16 value is the float32 result rounded once, and the
+    float32 result differs from the exact one by accumulation-order noise of at most 2^-19 of the summed
+    magnitudes, so |got - ref| <= 1 bf16 ulp (rounding, plus a possible step across a rounding boundary)
+    + 2^-19 * mag.  A dropped row, a wrong tap or a stale element fails this long before it moves the norm."""
+    got, ref, mag = (np.asarray(a, np.float64) for a in (got, ref, mag))
+    bound = bf16_ulp(ref) + 2.0 ** -19 * mag
+    bad = np.abs(got - ref) > bound
+    assert not bad.any(), (f"{name}: {int(bad.sum())} of {bad.size} elements outside 1 ulp + 2^-19 * magnitude; worst "
+                           f"{float(np.max(np.abs(got - ref) / bound)):.3g} x the bound at {np.argwhere(bad)[0].tolist()}")
 
 
 def rel_l2(got: np.ndarray, ref: np.ndarray) -> float:
@@ -137,14 +158,18 @@ def check_block(case, got, need_dx=True, addend=None, addend_mask=None, tol=None
     errs = {}
     y_o, z_o = orc.block_fwd(d, case["x"], case["w"], case["scale"], case["shift"], case["res"], return_z=True)
     errs["y"] = rel_l2(got["y"], y_o)
-    # ReLU mask: identical outside a band of pre-activations within fp32 accumulation noise of zero
-    if d.relu:
-        v = case["scale"].astype(np.float64)[None, :, None, None] * z_o + \
-            case["shift"].astype(np.float64)[None, :, None, None] + (case["res"] if case["res"] is not None else 0.0)
+    mag = None
+    if d.relu or bf16:
         mag = np.abs(case["scale"]).astype(np.float64)[None, :, None, None] * \
             orc.conv(d, np.abs(case["x"]), np.abs(case["w"])) + \
             np.abs(case["shift"]).astype(np.float64)[None, :, None, None] + \
             (np.abs(case["res"]) if case["res"] is not None else 0.0)
+    if bf16:
+        assert_elementwise_bf16("y", got["y"], y_o, mag)
+    # ReLU mask: identical outside a band of pre-activations within fp32 accumulation noise of zero
+    if d.relu:
+        v = case["scale"].astype(np.float64)[None, :, None, None] * z_o + \
+            case["shift"].astype(np.float64)[None, :, None, None] + (case["res"] if case["res"] is not None else 0.0)
         band = np.abs(v) <= 2.0 ** -19 * mag          # fp32 accumulation-order noise around zero
         mism = ((got["y"] > 0) != (v > 0)) & ~band
         assert not mism.any(), f"{int(mism.sum())} ReLU mask mismatches outside the rounding band"
@@ -168,12 +193,28 @@ def check_block(case, got, need_dx=True, addend=None, addend_mask=None, tol=None
             assert np.all(got["dx"][dx_mask <= 0] == 0), "dx not exactly zero where the mask is <= 0"
             dx_o = np.where(dx_mask > 0, dx_o, 0.0)
         errs["dx"] = rel_l2(got["dx"], dx_o)
+        if bf16:
+            # element by element against the same definition with the weights the data gradient multiplies:
+            # scale[co] * W rounded once to bf16 (product taken in float32, as on the GPU)
+            wf = wl.snap_to_bf16(case["scale"].astype(np.float32)[:, None, None, None] * case["w"].astype(np.float32))
+            one = np.ones(d.C_out)
+            dn = orc.Desc(d.N, d.H, d.W, d.C_in, d.C_out, d.KH, d.KW, d.stride, d.pad, False)
+            gm = g["dres"]                                           # the masked gradient
+            ref = orc.block_bwd(dn, gm, case["x"], wf, got["y"], one)["dx"]
+            dmag = orc.block_bwd(dn, np.abs(gm), case["x"], np.abs(wf), got["y"], one)["dx"]
+            if addend is not None:
+                a = np.where(addend_mask > 0, addend, 0.0) if addend_mask is not None else addend
+                ref, dmag = ref + a, dmag + np.abs(a)
+            if dx_mask is not None:
+                ref, dmag = np.where(dx_mask > 0, ref, 0.0), np.where(dx_mask > 0, dmag, 0.0)
+            assert_elementwise_bf16("dx", got["dx"], ref, dmag)
     errs["dW"] = rel_l2(got["dW"], g["dW"])
     errs["dscale"] = rel_l2(got["dscale"], g["dscale"])
     errs["dshift"] = rel_l2(got["dshift"], g["dshift"])
     if got.get("dres") is not None:
         assert np.array_equal(got["dres"], g["dres"]), "dres is not bit-exact"
         errs["dres"] = 0.0
-    bad = {k: v for k, v in errs.items() if k != "mask_band" and v > tol}
+    f32_out = ("dW", "dscale", "dshift")
+    bad = {k: v for k, v in errs.items() if k != "mask_band" and v > (min(tol, TOL_F32_OUTPUTS) if k in f32_out else tol)}
     assert not bad, f"relative L2 above {tol}: {bad} (all: {errs})"
     return errs

@@ -18,7 +18,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = declared_symbols()
-    assert set(names) == set(B.EXPORTS) and len(names) == 9
+    assert set(names) == set(B.EXPORTS) and len(names) == len(B.EXPORTS) >= 10
     lib = B.lib()
     for n in names:
         assert getattr(lib, n) is not None

@@ -81,6 +81,59 @@ def test_bf16_resnet50_layer_shapes(spec):
     show(name, pu.check_block(case, got, need_dx=(name != "stem")))
 
 
+@pytest.mark.parametrize("spec", RESNET_SHAPES[1:], ids=[s[0] for s in RESNET_SHAPES[1:]])
+def test_bf16_resnet50_layer_shapes_layer_merged_backward(spec):
+    """The same shapes the way the sequencer runs them backward: the gradient arrives already masked, the
+    block is called without SOL_RELU and without y, a shortcut gradient is added and the stored dx is masked
+    by the block input.  With channel counts that are multiples of 64 this is the pipelined data-gradient
+    and weight-gradient path (the call above, which masks dy itself, takes the general kernels)."""
+    name, c_in, c_out, h, k, stride, pad, res = spec
+    n = 1 if h >= 56 else (2 if h >= 14 else 5)
+    relu = "proj" not in name
+    case = pu.make_case(200 + len(name), n, h, h, c_in, c_out, k, stride, pad, relu=relu, res=res)
+    r = np.random.default_rng(201)
+    dxm = wl.snap_to_bf16(np.maximum(r.standard_normal(case["x"].shape), 0).astype(np.float32))
+    ad = wl.snap_to_bf16(r.standard_normal(case["x"].shape).astype(np.float32))
+    got = pu.gpu_block(case, addend=ad, dx_mask=dxm, premasked=True)
+    show(name + " merged", pu.check_block(case, got, addend=ad, dx_mask=dxm, premasked=True))
+
+
+PLAN_SHAPES = {
+    "3x3_s1_res_ragged": dict(N=2, H=19, W=17, C_in=64, C_out=136, K=3, stride=1, pad=1, res=True),
+    "3x3_s2": dict(N=2, H=15, W=13, C_in=64, C_out=64, K=3, stride=2, pad=1),
+    "1x1_s2_long_reduction": dict(N=2, H=14, W=14, C_in=512, C_out=256, K=1, stride=2, pad=0, relu=False),
+    "1x1_s1_many_rows": dict(N=3, H=14, W=14, C_in=128, C_out=192, K=1, stride=1, pad=0),
+}
+FAST_PLANS = [(t, s) for t in (0, 1, 2, 3) for s in (2, 3, 4) if not (t == 3 and s == 4)]
+
+
+@pytest.mark.parametrize("shape", list(PLAN_SHAPES), ids=list(PLAN_SHAPES))
+def test_every_installable_plan_matches_checker(shape):
+    """Every (tile, ring depth) a caller can install for the pipelined forward / data-gradient kernel and every
+    ring depth (and a few split counts) of the pipelined weight-gradient kernel, each compared with the CPU
+    checker -- not with the default plan's result."""
+    case = pu.make_case(81, **PLAN_SHAPES[shape])
+    d = case["d"]
+    desc = B.BlockDesc(d.N, d.H, d.W, d.C_in, d.C_out, d.KH, d.KW, d.stride, d.pad, B.SOL_BF16, 0)
+    r = np.random.default_rng(82)
+    dxm = wl.snap_to_bf16(np.maximum(r.standard_normal(case["x"].shape), 0).astype(np.float32))
+    ad = wl.snap_to_bf16(r.standard_normal(case["x"].shape).astype(np.float32))
+    wgrad_plans = [(2, 0), (3, 1), (4, 3), (2, 5), (3, 0), (4, 0)]
+    try:
+        for i, (tile, stages) in enumerate(FAST_PLANS):
+            ws, wsplit = wgrad_plans[i % len(wgrad_plans)]
+            B.sol_block_set_plan(desc, B.SOL_PLAN_FWD, (tile, stages, 0))
+            B.sol_block_set_plan(desc, B.SOL_PLAN_DGRAD, (tile, stages, 0))
+            B.sol_block_set_plan(desc, B.SOL_PLAN_WGRAD, (-1, ws, wsplit))
+            assert B.sol_block_get_plan(desc, B.SOL_PLAN_DGRAD) == (tile, stages, 0)
+            print(f"[plan] {shape}: tile {tile} stages {stages}; wgrad stages {ws} splits {wsplit}", flush=True)
+            got = pu.gpu_block(case, addend=ad, dx_mask=dxm, premasked=True)
+            errs = pu.check_block(case, got, addend=ad, dx_mask=dxm, premasked=True)
+        show(f"plans {shape} (last)", errs)
+    finally:
+        B.sol_clear_plans()
+
+
 @pytest.mark.parametrize("shape", [
     dict(N=1, H=1, W=1, C_in=8, C_out=8, K=3, stride=1, pad=1),               # single pixel, only the centre tap
     dict(N=3, H=5, W=7, C_in=16, C_out=24, K=3, stride=1, pad=1, res=True),   # fewer rows than one tile
@@ -103,16 +156,16 @@ def test_bf16_edge_shapes(shape):
 
 
 @pytest.mark.parametrize("tile", [0, 1, 2, 3])
-def test_bf16_every_tile_shape(tile, monkeypatch):
-    monkeypatch.setenv("SOL_IGEMM_TILE", str(tile))
+def test_bf16_every_tile_shape(tile, sol_env):
+    sol_env("SOL_IGEMM_TILE", tile)
     case = pu.make_case(9, 2, 19, 17, 32, 136, 3, 1, 1, res=True)
     got = pu.gpu_block(case)
     show(f"tile{tile}", pu.check_block(case, got))
 
 
 @pytest.mark.parametrize("splits", [1, 3, 50])
-def test_bf16_wgrad_split_counts(splits, monkeypatch):
-    monkeypatch.setenv("SOL_WGRAD_SPLITS", str(splits))
+def test_bf16_wgrad_split_counts(splits, sol_env):
+    sol_env("SOL_WGRAD_SPLITS", splits)
     case = pu.make_case(10, 2, 21, 19, 32, 40, 3, 1, 1)
     got = pu.gpu_block(case)
     show(f"splits{splits}", pu.check_block(case, got))
@@ -186,6 +239,11 @@ def test_few_channel_weight_gradient(shape):
     again = pu.gpu_block(case, need_dx=False, premasked=True)
     for k in ("dW", "dscale", "dshift"):
         assert np.array_equal(got[k], again[k]), k
+    init = np.random.default_rng(42).standard_normal(case["w"].shape).astype(np.float32)
+    acc = pu.gpu_block(case, need_dx=False, premasked=True, accumulate=True, dw_init=init)
+    np.testing.assert_allclose(acc["dW"], got["dW"] + init, rtol=1e-6, atol=1e-7)
+    np.testing.assert_allclose(acc["dscale"], got["dscale"] + 1.0, rtol=1e-6, atol=1e-7)
+    np.testing.assert_allclose(acc["dshift"], got["dshift"] - 2.0, rtol=1e-6, atol=1e-7)
 
 
 def test_untouched_pixels_take_addend_and_masks():

@@ -15,7 +15,12 @@ from oracle import oracle as orc                              # noqa: E402
 from paper_2205_10357_amd import binding as B, runner, tuning, workloads as wl      # noqa: E402
 from tests import parity_util as pu                           # noqa: E402
 
-TOL = 1e-2
+TOL = 1e-2              # bf16 tensors (y, dx)
+TOL_F32 = 1e-5          # float32 outputs (dW, dscale, dshift): float32 sums of exact bf16 products
+
+
+def over_tolerance(worst):
+    return {k: v for k, v in worst.items() if v > (TOL_F32 if k.rsplit(".", 1)[-1] in ("dW", "dscale", "dshift") else TOL)}
 
 
 def host(t, images=None):
@@ -98,7 +103,7 @@ def check_chain_elementwise(w):
         if last.relu:
             dy_o = np.where(acts[last.out] > 0, dy_o, 0.0)
         assert np.array_equal(dacts[last.out], orc.quantize_bf16(dy_o))
-    bad = {k: v for k, v in worst.items() if v > TOL}
+    bad = over_tolerance(worst)
     print(f"[parity] {w.name} N={n}: worst {max(worst.values()):.3g} over {len(worst)} tensors", flush=True)
     assert not bad, bad
     return seq, acts
@@ -217,7 +222,7 @@ def check_sampled(w, images, n_fwd=400, n_dx=300, dw_layers=(), n_dw=64, n_ch=2,
         worst[f"{o.name}.dscale"] = rel(runner.download(seq.grads[o.layer]["dscale"])[ch], ds)
         worst[f"{o.name}.dshift"] = rel(runner.download(seq.grads[o.layer]["dshift"])[ch], db)
         del dy, y, x
-    bad = {k: v for k, v in worst.items() if v > TOL}
+    bad = over_tolerance(worst)
     print(f"[parity] {w.name} N={w.n} sampled: worst {max(worst.values()):.3g} over {len(worst)} checks", flush=True)
     assert not bad, bad
 
@@ -229,29 +234,34 @@ def test_bottleneck_full_size_sampled():
 
 def test_resnet50_full_size_sampled():
     """Workload 4 (N = 128, 224x224, inference): every layer's output on sampled elements of two images."""
-    check_sampled(wl.resnet50_infer_bf16(), images=(0, 127), n_fwd=300)
+    check_sampled(wl.resnet50_infer_bf16(), images=(0, 64, 127), n_fwd=300)
 
 
 def test_stage2_full_size_sampled():
     """Workload 5 (N = 128, training step over stage 2)."""
-    check_sampled(wl.stage2_train_bf16(), images=(0, 127),
+    check_sampled(wl.stage2_train_bf16(), images=(0, 64, 127),
                   dw_layers=("s2.b0.conv2", "s2.b0.proj", "s2.b0.conv3", "s2.b2.conv1"), n_dw=48)
 
 
-def test_two_lane_backward_matches_one_lane():
-    """Weight branches on a second stream (block by block behind the gradient they read): same bits."""
-    w = wl.stage2_train_bf16(n=2, hw=14)
+@pytest.mark.parametrize("which", ["stage2_small", "bottleneck_full"])
+def test_two_lane_backward_matches_one_lane(which):
+    """Weight branches on a second stream (block by block behind the gradient they read): same bits.  At the
+    benchmark size the kernels are long enough for a block's weight branch to still be running when the next
+    block's data branch starts, which is why the second lane needs a workspace of its own."""
+    w = wl.stage2_train_bf16(n=2, hw=14) if which == "stage2_small" else wl.bottleneck14_bf16()
     seq = runner.Sequencer(w, "cuda:0", retain_activations=True)
     seq.step()
     torch.cuda.synchronize()
     ref = {k: {n: t.clone() for n, t in v.items()} for k, v in seq.grads.items()}
     ref_d = {k: v.clone() for k, v in seq.dact.items()}
-    for it in range(2):
+    assert seq._ws_side is None
+    for it in range(3):
         for v in seq.grads.values():
             for t in v.values():
                 t.fill_(3.0)
         torch.cuda.synchronize()
         seq.step(lanes=2)
+        assert seq._ws_side is not None and seq._ws_side.data_ptr() != seq.ws.data_ptr()
         torch.cuda.synchronize()
         for k, v in ref.items():
             for n, t in v.items():

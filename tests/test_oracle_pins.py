@@ -323,6 +323,37 @@ def test_point_functions_agree_with_full_loops(kw):
     np.testing.assert_allclose(db, g["dshift"], rtol=1e-12, atol=1e-13)
 
 
+@pytest.mark.parametrize("kw", [dict(res=True), dict(stride=2, H=9, W=8, relu=True), dict(KH=7, KW=7, pad=3, stride=2, H=12, W=11),
+                                dict(KH=1, KW=1, pad=0, stride=1, relu=False)])
+def test_point_pre_activation_and_rounding_magnitude_against_library(kw):
+    """The single-output forward returns the pre-activation v (negative ones included) and the magnitude
+    |scale| * sum|x*w| + |shift| + |r| that sets the width of the rounding band in the full-size mask checks.
+    Both are pinned to torch's CPU float64 conv2d: v on the signed operands, the magnitude as the same
+    convolution of the absolute values (a magnitude that is too large would silently widen the band, one
+    that is too small would flag legitimate roundings; >= |v| alone pins neither)."""
+    torch = pytest.importorskip("torch")
+    d, x, w, scale, shift, res = rand_block(24, **kw)
+    r = rng(25)
+    p = np.stack([r.integers(0, s, size=60) for s in (d.N, d.C_out, d.Ho, d.Wo)], axis=1)
+    v, y, mag = orc.fwd_points(d, x, w, scale, shift, res, p)
+
+    def tconv(a, b):
+        return torch.nn.functional.conv2d(torch.tensor(a), torch.tensor(b), stride=d.stride, padding=d.pad).numpy()
+
+    sc, sh = scale[None, :, None, None], shift[None, :, None, None]
+    v_ref = sc * tconv(x, w) + sh + (res if res is not None else 0.0)
+    mag_ref = np.abs(sc) * tconv(np.abs(x), np.abs(w)) + np.abs(sh) + (np.abs(res) if res is not None else 0.0)
+    assert (v_ref[tuple(p.T)] < 0).any() and (v_ref[tuple(p.T)] > 0).any()
+    np.testing.assert_allclose(v, v_ref[tuple(p.T)], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(mag, mag_ref[tuple(p.T)], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(y, np.maximum(v_ref, 0.0)[tuple(p.T)] if d.relu else v_ref[tuple(p.T)], rtol=1e-12, atol=1e-13)
+    # a negative scale must enter the magnitude by its absolute value
+    v2, _, mag2 = orc.fwd_points(d, x, w, -scale, shift, res, p)
+    mag2_ref = np.abs(sc) * tconv(np.abs(x), np.abs(w)) + np.abs(sh) + (np.abs(res) if res is not None else 0.0)
+    np.testing.assert_allclose(mag2, mag2_ref[tuple(p.T)], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(v2, (-sc * tconv(x, w) + sh + (res if res is not None else 0.0))[tuple(p.T)], rtol=1e-12, atol=1e-13)
+
+
 def test_maxpool_matches_library():
     torch = pytest.importorskip("torch")
     x = rng(22).standard_normal((2, 3, 9, 10))
