@@ -60,7 +60,8 @@ typedef enum {
     SOL_ERR_ALIGN = -3,       /* a pointer is not 16-byte aligned                           */
     SOL_ERR_UNSUPPORTED = -4, /* unknown dtype / flag bits, tensor beyond 2^31-1 elements   */
     SOL_ERR_WORKSPACE = -5,   /* workspace missing or smaller than sol_block_workspace_bytes */
-    SOL_ERR_LAUNCH = -6       /* the HIP runtime reported an error at launch                */
+    SOL_ERR_LAUNCH = -6,      /* the HIP runtime reported an error at launch                */
+    SOL_ERR_SCRATCH_LIMIT = -7 /* sol_block_bwd_noalloc: the call needs more scratch than the built-in buffer holds */
 } sol_status;
 
 typedef struct {
@@ -118,6 +119,25 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
                   const float* scale, void* dres, const void* dx_addend,
                   const void* dx_addend_mask, const void* dx_mask, void* ws, size_t ws_bytes,
                   void* hip_stream);
+
+/*
+ * sol_block_bwd for callers that cannot allocate device memory and have no workspace to pass: code
+ * under HIP graph capture, tight serving / training loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and errors as sol_block_bwd without ws / ws_bytes: the scratch (re-packed
+ * weights, split partial sums) lives in a buffer of SOL_NOALLOC_SCRATCH_BYTES bytes that is part of
+ * the library's code object, one copy per GPU, held until the process ends.  The call allocates and
+ * frees nothing.  SOL_ERR_SCRATCH_LIMIT when sol_block_workspace_bytes(desc, SOL_PASS_BWD) exceeds
+ * that size (nothing is launched then); sol_block_bwd_noalloc_limit() returns the size.  The GPU the
+ * stream belongs to must be the current device of the calling thread.  Every call on a GPU uses that
+ * GPU's one buffer and finds the previous call's contents in it (the kernels overwrite what they read
+ * back): calls that may overlap in time on one GPU -- two streams, two threads -- race; order them.
+ */
+#define SOL_NOALLOC_SCRATCH_BYTES (40u << 20)
+SOL_API int sol_block_bwd_noalloc(const sol_block_desc* desc, const void* dy, const void* x, const void* W,
+                          const void* y, void* dx, float* dW, float* dscale, float* dshift,
+                          const float* scale, void* dres, const void* dx_addend,
+                          const void* dx_addend_mask, const void* dx_mask, void* hip_stream);
+SOL_API size_t sol_block_bwd_noalloc_limit(void);
 
 /* Bytes of caller-provided scratch the given pass needs for this descriptor (0 if the
  * descriptor is invalid: the pass itself then reports the error).  The answer depends on every

@@ -19,7 +19,7 @@ SOL_PLAN_FWD, SOL_PLAN_DGRAD, SOL_PLAN_WGRAD = 0, 1, 2
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsol_block.so")
 EXPORTS = ("sol_block_fwd", "sol_block_bwd", "sol_block_workspace_bytes", "sol_status_string",
            "sol_l1_loss_grad", "sol_maxpool_fwd", "sol_block_set_plan", "sol_block_get_plan", "sol_clear_plans",
-           "sol_reload_overrides")
+           "sol_reload_overrides", "sol_block_bwd_noalloc", "sol_block_bwd_noalloc_limit")
 
 _lib = None
 
@@ -81,6 +81,10 @@ def lib():
         l.sol_block_bwd.restype = C.c_int
         l.sol_block_bwd.argtypes = [C.POINTER(_CDesc), vp, vp, vp, vp, vp, fp, fp, fp, fp, vp, vp, vp, vp, vp,
                                     C.c_size_t, vp]
+        l.sol_block_bwd_noalloc.restype = C.c_int
+        l.sol_block_bwd_noalloc.argtypes = [C.POINTER(_CDesc), vp, vp, vp, vp, vp, fp, fp, fp, fp, vp, vp, vp, vp, vp]
+        l.sol_block_bwd_noalloc_limit.restype = C.c_size_t
+        l.sol_block_bwd_noalloc_limit.argtypes = []
         l.sol_block_workspace_bytes.restype = C.c_size_t
         l.sol_block_workspace_bytes.argtypes = [C.POINTER(_CDesc), C.c_int]
         l.sol_status_string.restype = C.c_char_p
@@ -190,6 +194,21 @@ def sol_block_bwd(desc, dy, x, W, y, dx, dW, dscale, dshift, scale, dres=None, d
     if check and st != 0:
         raise SolError(st, "sol_block_bwd")
     return st
+
+
+def sol_block_bwd_noalloc(desc, dy, x, W, y, dx, dW, dscale, dshift, scale, dres=None, dx_addend=None,
+                          dx_addend_mask=None, dx_mask=None, stream=None, check: bool = True) -> int:
+    d = _cdesc(desc)
+    st = lib().sol_block_bwd_noalloc(C.byref(d), _ptr(dy), _ptr(x), _ptr(W), _ptr(y), _ptr(dx), _ptr(dW),
+                                     _ptr(dscale), _ptr(dshift), _ptr(scale), _ptr(dres), _ptr(dx_addend),
+                                     _ptr(dx_addend_mask), _ptr(dx_mask), _stream(stream))
+    if check and st != 0:
+        raise SolError(st, "sol_block_bwd_noalloc")
+    return st
+
+
+def sol_block_bwd_noalloc_limit() -> int:
+    return int(lib().sol_block_bwd_noalloc_limit())
 
 
 def sol_l1_loss_grad(dtype: int, y, t, dy, numel: int, mask_by_y: bool = False, stream=None,

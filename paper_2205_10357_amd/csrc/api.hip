@@ -17,6 +17,7 @@ namespace sol {
 namespace {
 
 constexpr size_t kAlign = 256;
+int builtin_scratch_address(void** out);      // device address of this GPU's built-in scratch array
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
@@ -383,6 +384,39 @@ int dgrad_bf16(const sol_block_desc* d, const Geometry& g, const void* dy, const
 }  // namespace
 }  // namespace sol
 
+// ---- built-in scratch of the no-allocation backward entry point ---------------------------------------------
+// One array per GPU, part of the loaded code object (it exists on every device the library runs on until the
+// process ends).  In host code the array's NAME is only a stand-in: the device address is asked for once per
+// device, with that device current, and only that address is ever handed to kernels.
+static __device__ __align__(256) unsigned char scratch[SOL_NOALLOC_SCRATCH_BYTES];
+
+namespace sol {
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+int builtin_scratch_address(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SOL_ERR_LAUNCH;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+        if (!p) {
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+                (void)hipGetLastError();
+                return SOL_ERR_LAUNCH;
+            }
+            g_scratch_ptr[dev].store(p, std::memory_order_release);
+        }
+    }
+    *out = p;
+    return SOL_OK;
+}
+}  // namespace
+}  // namespace sol
+
 using namespace sol;
 
 extern "C" {
@@ -396,6 +430,7 @@ SOL_API const char* sol_status_string(int status) {
         case SOL_ERR_UNSUPPORTED: return "unsupported dtype, flag or size";
         case SOL_ERR_WORKSPACE: return "workspace missing or too small";
         case SOL_ERR_LAUNCH: return "HIP launch error";
+        case SOL_ERR_SCRATCH_LIMIT: return "the call needs more scratch than the no-allocation entry point's built-in buffer holds";
         default: return "unknown status";
     }
 }
@@ -434,6 +469,8 @@ SOL_API int sol_block_fwd(const sol_block_desc* desc, const void* x, const void*
     return launch_direct_fwd_f32(p, stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
 }
 
+// Both backward entry points: everything after the workspace has been chosen.  scratch_limit > 0 marks the
+// built-in buffer of the no-allocation entry point, whose size is a property of the library, not of the call.
 static int bwd_common(const sol_block_desc* desc, const void* dy, const void* x, const void* W, const void* y, void* dx,
                       float* dW, float* dscale, float* dshift, const float* scale, void* dres, const void* dx_addend,
                       const void* dx_addend_mask, const void* dx_mask, void* ws, size_t ws_bytes, bool builtin_scratch,
@@ -452,6 +489,10 @@ static int bwd_common(const sol_block_desc* desc, const void* dy, const void* x,
         return SOL_ERR_ALIGN;
     if (desc->dtype == SOL_BF16 && dx && desc->stride * desc->stride > kMaxClasses) return SOL_ERR_UNSUPPORTED;
     const BwdPlan plan = plan_bwd(desc, g);
+    if (builtin_scratch) {
+        if (plan.total > ws_bytes) return SOL_ERR_SCRATCH_LIMIT;
+        if (int e = builtin_scratch_address(&ws); e != SOL_OK) return e;
+    }
     if (!ws || ws_bytes < plan.total) return SOL_ERR_WORKSPACE;
     hipStream_t stream = (hipStream_t)hip_stream;
     clear_stale_error();
@@ -574,6 +615,15 @@ SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void
     return bwd_common(desc, dy, x, W, y, dx, dW, dscale, dshift, scale, dres, dx_addend, dx_addend_mask, dx_mask, ws,
                       ws_bytes, false, hip_stream);
 }
+
+SOL_API int sol_block_bwd_noalloc(const sol_block_desc* desc, const void* dy, const void* x, const void* W, const void* y,
+                          void* dx, float* dW, float* dscale, float* dshift, const float* scale, void* dres,
+                          const void* dx_addend, const void* dx_addend_mask, const void* dx_mask, void* hip_stream) {
+    return bwd_common(desc, dy, x, W, y, dx, dW, dscale, dshift, scale, dres, dx_addend, dx_addend_mask, dx_mask, nullptr,
+                      (size_t)SOL_NOALLOC_SCRATCH_BYTES, true, hip_stream);
+}
+
+SOL_API size_t sol_block_bwd_noalloc_limit(void) { return (size_t)SOL_NOALLOC_SCRATCH_BYTES; }
 
 SOL_API int sol_block_set_plan(const sol_block_desc* desc, int which, const sol_plan* plan) {
     if (!desc) return SOL_ERR_NULL;

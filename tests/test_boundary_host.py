@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_status_strings():
     assert B.sol_status_string(0) == "ok"
-    for s in range(-6, 0):
+    for s in range(-7, 0):
         assert B.sol_status_string(s) not in ("ok", "unknown status")
     assert B.sol_status_string(-99) == "unknown status"
 
