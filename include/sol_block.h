@@ -202,6 +202,66 @@ SOL_API int sol_l1_loss_grad(int32_t dtype, const void* y, const void* t, void* 
 SOL_API int sol_maxpool_fwd(int32_t dtype, const void* x, void* y, int32_t N, int32_t H, int32_t W,
                     int32_t C, int32_t k, int32_t stride, int32_t pad, void* hip_stream);
 
+/*
+ * Prepared sequences.  The paper's compiled network is one library call that runs a static schedule
+ * (section "SOL architecture": the generated library holds the whole execution pipeline; section on
+ * memory consumption: the schedule is static).  A sequence is that schedule for this library: the
+ * caller records the block calls of a pass once, with their final buffers, and sol_sequence_run then
+ * issues calls [first, first + count) in order on one stream without returning to the caller between
+ * launches.  Recording validates nothing and touches no device; every recorded call behaves exactly
+ * like the entry point it names when it is run (same checks, same errors: run stops at the first
+ * failing call and returns its status).  The sequence keeps copies of the descriptors and of the
+ * pointer VALUES only; the buffers stay the caller's and must outlive the runs.  A sequence is a
+ * host object (sol_sequence_create / sol_sequence_destroy); running one sequence from two threads at
+ * once is safe only if the recorded calls may overlap (see the workspace rule of sol_block_bwd).
+ * tag: any number; it labels the launches of that call in a launch trace.
+ */
+typedef struct sol_sequence sol_sequence;
+SOL_API sol_sequence* sol_sequence_create(void);                 /* NULL when out of host memory */
+SOL_API void sol_sequence_destroy(sol_sequence* seq);            /* NULL is allowed */
+SOL_API int32_t sol_sequence_length(const sol_sequence* seq);
+SOL_API int sol_sequence_add_fwd(sol_sequence* seq, const sol_block_desc* desc, const void* x, const void* W,
+                         const float* scale, const float* shift, const void* residual, void* y, void* ws,
+                         size_t ws_bytes, int32_t tag);
+SOL_API int sol_sequence_add_bwd(sol_sequence* seq, const sol_block_desc* desc, const void* dy, const void* x,
+                         const void* W, const void* y, void* dx, float* dW, float* dscale, float* dshift,
+                         const float* scale, void* dres, const void* dx_addend, const void* dx_addend_mask,
+                         const void* dx_mask, void* ws, size_t ws_bytes, int32_t tag);
+SOL_API int sol_sequence_add_l1_loss_grad(sol_sequence* seq, int32_t dtype, const void* y, const void* t, void* dy,
+                                  int64_t numel, int32_t mask_by_y, int32_t tag);
+SOL_API int sol_sequence_add_maxpool(sol_sequence* seq, int32_t dtype, const void* x, void* y, int32_t N, int32_t H,
+                             int32_t W, int32_t C, int32_t k, int32_t stride, int32_t pad, int32_t tag);
+SOL_API int sol_sequence_run(const sol_sequence* seq, int32_t first, int32_t count, void* hip_stream);
+
+/*
+ * Launch trace: GPU time of every kernel launch the library makes, in launch order, without an external
+ * profiler (the per-layer timing that the paper's auto-tuning relies on, section "SOL architecture").
+ * Between sol_trace_start and sol_trace_stop every launch carries a start and a stop event of its own,
+ * stamped from the dispatch itself (no barrier between kernels, so the step runs as it does untraced and
+ * the times are the kernels' execution times, as a profiler reports them).  sol_trace_stop waits for the
+ * launches and returns, per launch in launch order: its kind, the tag that was current when it was issued
+ * (sol_trace_tag, or the tag of the sequence call), its execution time and its start relative to the
+ * first traced launch, both in microseconds.  capacity of sol_trace_start = launches to provide events
+ * for; launches beyond it run untraced.  The events are created by sol_trace_start (the only place in the
+ * library that creates HIP objects) and kept for later traces.
+ * One trace at a time, all calls traced must use one stream; not for use under graph capture.
+ */
+enum {
+    SOL_TRACE_OTHER = 0, SOL_TRACE_IGEMM, SOL_TRACE_IGEMM_GENERAL, SOL_TRACE_WGRAD, SOL_TRACE_WGRAD_GENERAL,
+    SOL_TRACE_WGRAD_REDUCE, SOL_TRACE_PACK, SOL_TRACE_UNTOUCHED, SOL_TRACE_MASKED_COPY, SOL_TRACE_SMALLC_PREPARE,
+    SOL_TRACE_SMALLC_FWD, SOL_TRACE_SMALLC_WGRAD, SOL_TRACE_DIRECT, SOL_TRACE_L1_GRAD, SOL_TRACE_MAXPOOL
+};
+typedef struct {
+    int32_t kind;   /* SOL_TRACE_* */
+    int32_t tag;
+    float us;       /* execution time of the launch            */
+    float start_us; /* its start, counted from the first launch */
+} sol_trace_entry;
+SOL_API int sol_trace_start(int32_t capacity);
+SOL_API void sol_trace_tag(int32_t tag);
+SOL_API int sol_trace_stop(sol_trace_entry* out, int32_t capacity, int32_t* count);
+SOL_API const char* sol_trace_kind_name(int32_t kind);
+
 #ifdef __cplusplus
 }
 #endif

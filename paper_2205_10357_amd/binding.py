@@ -19,7 +19,10 @@ SOL_PLAN_FWD, SOL_PLAN_DGRAD, SOL_PLAN_WGRAD = 0, 1, 2
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsol_block.so")
 EXPORTS = ("sol_block_fwd", "sol_block_bwd", "sol_block_workspace_bytes", "sol_status_string",
            "sol_l1_loss_grad", "sol_maxpool_fwd", "sol_block_set_plan", "sol_block_get_plan", "sol_clear_plans",
-           "sol_reload_overrides", "sol_block_bwd_noalloc", "sol_block_bwd_noalloc_limit")
+           "sol_reload_overrides", "sol_block_bwd_noalloc", "sol_block_bwd_noalloc_limit",
+           "sol_sequence_create", "sol_sequence_destroy", "sol_sequence_length", "sol_sequence_add_fwd",
+           "sol_sequence_add_bwd", "sol_sequence_add_l1_loss_grad", "sol_sequence_add_maxpool", "sol_sequence_run",
+           "sol_trace_start", "sol_trace_tag", "sol_trace_stop", "sol_trace_kind_name")
 
 _lib = None
 
@@ -34,6 +37,10 @@ class _CDesc(C.Structure):
     _fields_ = [("N", C.c_int32), ("H", C.c_int32), ("W", C.c_int32), ("C_in", C.c_int32),
                 ("C_out", C.c_int32), ("KH", C.c_int32), ("KW", C.c_int32),
                 ("stride", C.c_int32), ("pad", C.c_int32), ("dtype", C.c_int32), ("flags", C.c_uint32)]
+
+
+class _CTraceEntry(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("tag", C.c_int32), ("us", C.c_float), ("start_us", C.c_float)]
 
 
 class _CPlan(C.Structure):
@@ -85,6 +92,32 @@ def lib():
         l.sol_block_bwd_noalloc.argtypes = [C.POINTER(_CDesc), vp, vp, vp, vp, vp, fp, fp, fp, fp, vp, vp, vp, vp, vp]
         l.sol_block_bwd_noalloc_limit.restype = C.c_size_t
         l.sol_block_bwd_noalloc_limit.argtypes = []
+        i32 = C.c_int32
+        l.sol_sequence_create.restype = vp
+        l.sol_sequence_create.argtypes = []
+        l.sol_sequence_destroy.restype = None
+        l.sol_sequence_destroy.argtypes = [vp]
+        l.sol_sequence_length.restype = i32
+        l.sol_sequence_length.argtypes = [vp]
+        l.sol_sequence_add_fwd.restype = C.c_int
+        l.sol_sequence_add_fwd.argtypes = [vp, C.POINTER(_CDesc), vp, vp, fp, fp, vp, vp, vp, C.c_size_t, i32]
+        l.sol_sequence_add_bwd.restype = C.c_int
+        l.sol_sequence_add_bwd.argtypes = [vp, C.POINTER(_CDesc), vp, vp, vp, vp, vp, fp, fp, fp, fp, vp, vp, vp, vp, vp,
+                                           C.c_size_t, i32]
+        l.sol_sequence_add_l1_loss_grad.restype = C.c_int
+        l.sol_sequence_add_l1_loss_grad.argtypes = [vp, i32, vp, vp, vp, C.c_int64, i32, i32]
+        l.sol_sequence_add_maxpool.restype = C.c_int
+        l.sol_sequence_add_maxpool.argtypes = [vp, i32, vp, vp] + [i32] * 8
+        l.sol_sequence_run.restype = C.c_int
+        l.sol_sequence_run.argtypes = [vp, i32, i32, vp]
+        l.sol_trace_start.restype = C.c_int
+        l.sol_trace_start.argtypes = [i32]
+        l.sol_trace_tag.restype = None
+        l.sol_trace_tag.argtypes = [i32]
+        l.sol_trace_stop.restype = C.c_int
+        l.sol_trace_stop.argtypes = [C.POINTER(_CTraceEntry), i32, C.POINTER(i32)]
+        l.sol_trace_kind_name.restype = C.c_char_p
+        l.sol_trace_kind_name.argtypes = [i32]
         l.sol_block_workspace_bytes.restype = C.c_size_t
         l.sol_block_workspace_bytes.argtypes = [C.POINTER(_CDesc), C.c_int]
         l.sol_status_string.restype = C.c_char_p
@@ -226,3 +259,85 @@ def sol_maxpool_fwd(dtype: int, x, y, N: int, H: int, W: int, Cc: int, k: int, s
     if check and st != 0:
         raise SolError(st, "sol_maxpool_fwd")
     return st
+
+
+class Sequence:
+    """A prepared list of block calls (sol_sequence_*): record once, run with one call per pass."""
+
+    def __init__(self):
+        self._h = lib().sol_sequence_create()
+        if not self._h:
+            raise MemoryError("sol_sequence_create")
+        self._keep = []                      # the recorded buffers must outlive the runs
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.sol_sequence_destroy(self._h)
+            self._h = None
+
+    def __len__(self) -> int:
+        return int(lib().sol_sequence_length(self._h))
+
+    def _ok(self, st: int, where: str) -> None:
+        if st != 0:
+            raise SolError(st, where)
+
+    def add_fwd(self, desc, x, W, scale, shift, residual, y, ws=None, ws_bytes: Optional[int] = None, tag: int = 0):
+        d = _cdesc(desc)
+        nb = _nbytes(ws) if ws_bytes is None else ws_bytes
+        self._keep.append((x, W, scale, shift, residual, y, ws))
+        self._ok(lib().sol_sequence_add_fwd(self._h, C.byref(d), _ptr(x), _ptr(W), _ptr(scale), _ptr(shift),
+                                            _ptr(residual), _ptr(y), _ptr(ws), nb, int(tag)), "sol_sequence_add_fwd")
+
+    def add_bwd(self, desc, dy, x, W, y, dx, dW, dscale, dshift, scale, dres=None, dx_addend=None,
+                dx_addend_mask=None, dx_mask=None, ws=None, ws_bytes: Optional[int] = None, tag: int = 0):
+        d = _cdesc(desc)
+        nb = _nbytes(ws) if ws_bytes is None else ws_bytes
+        self._keep.append((dy, x, W, y, dx, dW, dscale, dshift, scale, dres, dx_addend, dx_addend_mask, dx_mask, ws))
+        self._ok(lib().sol_sequence_add_bwd(self._h, C.byref(d), _ptr(dy), _ptr(x), _ptr(W), _ptr(y), _ptr(dx),
+                                            _ptr(dW), _ptr(dscale), _ptr(dshift), _ptr(scale), _ptr(dres),
+                                            _ptr(dx_addend), _ptr(dx_addend_mask), _ptr(dx_mask), _ptr(ws), nb,
+                                            int(tag)), "sol_sequence_add_bwd")
+
+    def add_l1_loss_grad(self, dtype: int, y, t, dy, numel: int, mask_by_y: bool = False, tag: int = 0):
+        self._keep.append((y, t, dy))
+        self._ok(lib().sol_sequence_add_l1_loss_grad(self._h, int(dtype), _ptr(y), _ptr(t), _ptr(dy), int(numel),
+                                                     int(bool(mask_by_y)), int(tag)), "sol_sequence_add_l1_loss_grad")
+
+    def add_maxpool(self, dtype: int, x, y, N: int, H: int, W: int, Cc: int, k: int, stride: int, pad: int,
+                    tag: int = 0):
+        self._keep.append((x, y))
+        self._ok(lib().sol_sequence_add_maxpool(self._h, int(dtype), _ptr(x), _ptr(y), N, H, W, Cc, k, stride, pad,
+                                                int(tag)), "sol_sequence_add_maxpool")
+
+    def run(self, first: int = 0, count: Optional[int] = None, stream=None, check: bool = True) -> int:
+        n = len(self) - first if count is None else count
+        st = lib().sol_sequence_run(self._h, int(first), int(n), _stream(stream))
+        if check and st != 0:
+            raise SolError(st, "sol_sequence_run")
+        return st
+
+
+def sol_trace_start(capacity: int = 4096) -> None:
+    st = lib().sol_trace_start(int(capacity))
+    if st != 0:
+        raise SolError(st, "sol_trace_start")
+
+
+def sol_trace_tag(tag: int) -> None:
+    lib().sol_trace_tag(int(tag))
+
+
+def sol_trace_stop(capacity: int = 4096):
+    """-> list of (kind, tag, execution microseconds, start microseconds since the first launch) in launch order."""
+    buf = (_CTraceEntry * capacity)()
+    n = C.c_int32(0)
+    st = lib().sol_trace_stop(buf, int(capacity), C.byref(n))
+    if st != 0:
+        raise SolError(st, "sol_trace_stop")
+    return [(int(buf[i].kind), int(buf[i].tag), float(buf[i].us), float(buf[i].start_us))
+            for i in range(min(n.value, capacity))]
+
+
+def sol_trace_kind_name(kind: int) -> str:
+    return lib().sol_trace_kind_name(int(kind)).decode()

@@ -184,6 +184,7 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& 
     }
     p.total_tiles = tiles_p * p.tiles_c;
     hipError_t e;
+    trace_point(stream, fast_ok ? SOL_TRACE_IGEMM : SOL_TRACE_IGEMM_GENERAL);
     if (fast_ok) e = launch_igemm_fast(p, tile, stages, stream);
     else e = launch_igemm(p, tile, (p.Cs % 8) == 0, mask, stream);
     return e == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
@@ -270,7 +271,9 @@ int fwd_bf16(const sol_block_desc* d, const Geometry& g, const void* x, const vo
         SmallCParams sp{(const bf16_t*)x, (bf16_t*)(wsb + plan.xp_off), (const bf16_t*)W, (bf16_t*)(wsb + plan.wp_off),
                         scale, shift, (bf16_t*)y, d->N, d->H, d->W, d->C_in, d->KH, d->KW, d->pad, g.Ho, g.Wo,
                         (d->flags & SOL_RELU) ? 1 : 0};
+        trace_point(stream, SOL_TRACE_SMALLC_PREPARE);
         if (launch_smallc_prepare(sp, stream) != hipSuccess) return SOL_ERR_LAUNCH;
+        trace_point(stream, SOL_TRACE_SMALLC_FWD);
         return launch_smallc_fwd(sp, stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
     }
     IgemmParams p{};
@@ -374,6 +377,7 @@ int dgrad_bf16(const sol_block_desc* d, const Geometry& g, const void* dy, const
             ++nc;
         }
     p.ncls = nc;
+    if (any_untouched) trace_point(stream, SOL_TRACE_UNTOUCHED);
     if (any_untouched &&
         launch_untouched_pixels(dx, addend, addend_mask, dx_mask, d->N, d->H, d->W, d->C_in, d->KH, d->KW, s, d->pad,
                                 stream) != hipSuccess)
@@ -455,7 +459,10 @@ SOL_API int sol_block_fwd(const sol_block_desc* desc, const void* x, const void*
     if (need > 0 && (!ws || ws_bytes < need)) return SOL_ERR_WORKSPACE;
     hipStream_t stream = (hipStream_t)hip_stream;
     clear_stale_error();
-    if (desc->dtype == SOL_BF16) return fwd_bf16(desc, g, x, W, scale, shift, residual, y, ws, stream);
+    if (desc->dtype == SOL_BF16) {
+        const int st = fwd_bf16(desc, g, x, W, scale, shift, residual, y, ws, stream);
+            return st;
+    }
     DirectParams p{};
     p.x = (const float*)x;
     p.W = (const float*)W;
@@ -466,7 +473,9 @@ SOL_API int sol_block_fwd(const sol_block_desc* desc, const void* x, const void*
     p.N = desc->N; p.H = desc->H; p.W_ = desc->W; p.C_in = desc->C_in; p.C_out = desc->C_out;
     p.KH = desc->KH; p.KW = desc->KW; p.stride = desc->stride; p.pad = desc->pad;
     p.Ho = g.Ho; p.Wo = g.Wo; p.relu = (desc->flags & SOL_RELU) ? 1 : 0;
-    return launch_direct_fwd_f32(p, stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
+    trace_point(stream, SOL_TRACE_DIRECT);
+    const int st = launch_direct_fwd_f32(p, stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
+    return st;
 }
 
 // Both backward entry points: everything after the workspace has been chosen.  scratch_limit > 0 marks the
@@ -530,14 +539,17 @@ static int bwd_common(const sol_block_desc* desc, const void* dy, const void* x,
 
     // ---- data branch: shortcut gradient, weight re-pack, data-gradient GEMM ----
     auto data_branch = [&](hipStream_t st) -> int {
+        if (dres) trace_point(st, SOL_TRACE_MASKED_COPY);
         if (dres && launch_masked_copy(desc->dtype, dy, ymask, dres, g.y_elems, st) != hipSuccess)
             return SOL_ERR_LAUNCH;
         if (!dx) return SOL_OK;
         if (desc->dtype == SOL_BF16) {
+            if (!pack_rides) trace_point(st, SOL_TRACE_PACK);
             if (!pack_rides && launch_pack_dgrad_weights(pk, st) != hipSuccess) return SOL_ERR_LAUNCH;
             return dgrad_bf16(desc, g, dy, y, pk.out, dx, dx_addend, dx_addend_mask, dx_mask, st);
         }
         DirectParams p = direct_params();
+        trace_point(st, SOL_TRACE_DIRECT);
         return launch_direct_dgrad_f32(p, st) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
     };
 
@@ -547,7 +559,9 @@ static int bwd_common(const sol_block_desc* desc, const void* dy, const void* x,
             bf16_t* xp = (bf16_t*)(wsb + plan.sc_xp_off);
             SmallCParams pp{(const bf16_t*)x, xp, (const bf16_t*)W, nullptr, scale, nullptr, nullptr, desc->N, desc->H,
                             desc->W, desc->C_in, desc->KH, desc->KW, desc->pad, g.Ho, g.Wo, 0};
+            trace_point(st, SOL_TRACE_SMALLC_PREPARE);
             if (launch_smallc_prepare(pp, st) != hipSuccess) return SOL_ERR_LAUNCH;
+            trace_point(st, SOL_TRACE_SMALLC_WGRAD);
             SmallCWgradParams wp{(const bf16_t*)dy, xp, (const bf16_t*)W, scale, (float*)(wsb + plan.sc_part_off), dW,
                                  dscale, dshift, desc->N, desc->H, desc->W, desc->C_in, desc->KH, desc->KW, desc->pad,
                                  g.Ho, g.Wo, plan.sc_parts, (desc->flags & SOL_DW_ACCUMULATE) ? 1 : 0};
@@ -576,12 +590,15 @@ static int bwd_common(const sol_block_desc* desc, const void* dy, const void* x,
                 if (stages < 2 || stages > 4) stages = installed_plan(desc, SOL_PLAN_WGRAD).stages;
                 if (stages < 2 || stages > 4)
                     stages = (desc->KH == 1 && desc->KW == 1 && desc->stride == 1 && desc->pad == 0) ? 3 : 2;
+                trace_point(st, SOL_TRACE_WGRAD);
                 if (launch_wgrad_fast(wp, stages, st) != hipSuccess) return SOL_ERR_LAUNCH;
-            } else if (launch_wgrad(wp, vec, relu, st) != hipSuccess) {
-                return SOL_ERR_LAUNCH;
+            } else {
+                trace_point(st, SOL_TRACE_WGRAD_GENERAL);
+                if (launch_wgrad(wp, vec, relu, st) != hipSuccess) return SOL_ERR_LAUNCH;
             }
         } else {
             DirectParams p = direct_params();
+            trace_point(st, SOL_TRACE_DIRECT);
             if (launch_direct_wgrad_f32(p, st) != hipSuccess) return SOL_ERR_LAUNCH;
         }
         ReduceParams rp{};
@@ -597,16 +614,20 @@ static int bwd_common(const sol_block_desc* desc, const void* dy, const void* x,
         rp.splits = plan.splits;
         rp.accumulate = (desc->flags & SOL_DW_ACCUMULATE) ? 1 : 0;
         rp.w_is_bf16 = desc->dtype == SOL_BF16 ? 1 : 0;
+        trace_point(st, SOL_TRACE_WGRAD_REDUCE);
         return launch_wgrad_reduce(rp, st) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
     };
 
     // the two branches share only inputs (dy, x, W, scale) and use disjoint parts of the workspace
+    int status;
     if (pack_rides) {
-        if (int e = weight_branch(stream); e != SOL_OK) return e;
-        return data_branch(stream);
+        status = weight_branch(stream);
+        if (status == SOL_OK) status = data_branch(stream);
+    } else {
+        status = data_branch(stream);
+        if (status == SOL_OK && dW) status = weight_branch(stream);
     }
-    if (int e = data_branch(stream); e != SOL_OK) return e;
-    return dW ? weight_branch(stream) : SOL_OK;
+    return status;
 }
 
 SOL_API int sol_block_bwd(const sol_block_desc* desc, const void* dy, const void* x, const void* W, const void* y, void* dx,
@@ -665,7 +686,9 @@ SOL_API int sol_l1_loss_grad(int32_t dtype, const void* y, const void* t, void* 
     if (!y || !t || !dy) return SOL_ERR_NULL;
     if (misaligned(y) || misaligned(t) || misaligned(dy)) return SOL_ERR_ALIGN;
     clear_stale_error();
-    return launch_l1_grad(dtype, y, t, dy, numel, mask_by_y, (hipStream_t)hip_stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
+    trace_point((hipStream_t)hip_stream, SOL_TRACE_L1_GRAD);
+    const int st = launch_l1_grad(dtype, y, t, dy, numel, mask_by_y, (hipStream_t)hip_stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
+    return st;
 }
 
 SOL_API int sol_maxpool_fwd(int32_t dtype, const void* x, void* y, int32_t N, int32_t H, int32_t W, int32_t C, int32_t k,
@@ -677,8 +700,10 @@ SOL_API int sol_maxpool_fwd(int32_t dtype, const void* x, void* y, int32_t N, in
     if (!x || !y) return SOL_ERR_NULL;
     if (misaligned(x) || misaligned(y)) return SOL_ERR_ALIGN;
     clear_stale_error();
-    return launch_maxpool(dtype, x, y, N, H, W, C, k, stride, pad, (hipStream_t)hip_stream) == hipSuccess
-               ? SOL_OK : SOL_ERR_LAUNCH;
+    trace_point((hipStream_t)hip_stream, SOL_TRACE_MAXPOOL);
+    const int st = launch_maxpool(dtype, x, y, N, H, W, C, k, stride, pad, (hipStream_t)hip_stream) == hipSuccess
+                       ? SOL_OK : SOL_ERR_LAUNCH;
+    return st;
 }
 
 }  // extern "C"

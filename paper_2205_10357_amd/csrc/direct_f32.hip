@@ -121,17 +121,17 @@ __global__ __launch_bounds__(256) void direct_colsum_f32(const DirectParams p) {
 static inline unsigned blocks_for(long long total) { return (unsigned)((total + 255) / 256); }
 
 hipError_t launch_direct_fwd_f32(const DirectParams& p, hipStream_t s) {
-    hipLaunchKernelGGL(direct_fwd_f32, dim3(blocks_for((long long)p.N * p.Ho * p.Wo * p.C_out)), dim3(256), 0, s, p);
+    SOL_LAUNCH(direct_fwd_f32, dim3(blocks_for((long long)p.N * p.Ho * p.Wo * p.C_out)), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 hipError_t launch_direct_dgrad_f32(const DirectParams& p, hipStream_t s) {
-    hipLaunchKernelGGL(direct_dgrad_f32, dim3(blocks_for((long long)p.N * p.H * p.W_ * p.C_in)), dim3(256), 0, s, p);
+    SOL_LAUNCH(direct_dgrad_f32, dim3(blocks_for((long long)p.N * p.H * p.W_ * p.C_in)), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 hipError_t launch_direct_wgrad_f32(const DirectParams& p, hipStream_t s) {
-    hipLaunchKernelGGL(direct_wgrad_f32, dim3(blocks_for((long long)p.C_out * p.KH * p.KW * p.C_in)), dim3(256), 0, s, p);
+    SOL_LAUNCH(direct_wgrad_f32, dim3(blocks_for((long long)p.C_out * p.KH * p.KW * p.C_in)), dim3(256), 0, s, p);
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
-    hipLaunchKernelGGL(direct_colsum_f32, dim3(p.C_out), dim3(256), 0, s, p);
+    SOL_LAUNCH(direct_colsum_f32, dim3(p.C_out), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 

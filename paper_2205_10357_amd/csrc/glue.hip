@@ -139,7 +139,7 @@ hipError_t launch_untouched_pixels(void* dx, const void* addend, const void* add
                                    int H, int W, int C, int KH, int KW, int stride, int pad, hipStream_t s) {
     const long long total = (long long)N * H * W * (C >> 3);
     if (total <= 0) return hipSuccess;
-    hipLaunchKernelGGL(untouched_pixels_kernel, dim3(blocks_for(total)), dim3(256), 0, s, (bf16_t*)dx,
+    SOL_LAUNCH(untouched_pixels_kernel, dim3(blocks_for(total)), dim3(256), 0, s, (bf16_t*)dx,
                        (const bf16_t*)addend, (const bf16_t*)addend_mask, (const bf16_t*)out_mask, N, H, W, C, KH, KW,
                        stride, pad);
     return hipGetLastError();
@@ -148,19 +148,19 @@ hipError_t launch_untouched_pixels(void* dx, const void* addend, const void* add
 hipError_t launch_pack_dgrad_weights(const PackParams& p, hipStream_t s) {
     const long long total = (long long)p.C_out * p.KH * p.KW * p.C_in;
     if ((p.C_in & 63) == 0 && (p.C_out & 63) == 0)
-        hipLaunchKernelGGL(pack_dgrad_weights_tiled_kernel, dim3((unsigned)pack_tile_count(p)), dim3(256), 0, s, p);
+        SOL_LAUNCH(pack_dgrad_weights_tiled_kernel, dim3((unsigned)pack_tile_count(p)), dim3(256), 0, s, p);
     else
-        hipLaunchKernelGGL(pack_dgrad_weights_kernel, dim3(blocks_for(total)), dim3(256), 0, s, p);
+        SOL_LAUNCH(pack_dgrad_weights_kernel, dim3(blocks_for(total)), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
 hipError_t launch_masked_copy(int dtype, const void* dy, const void* y, void* dres, long long numel, hipStream_t s) {
     if (numel <= 0) return hipSuccess;
     if (dtype == 1)
-        hipLaunchKernelGGL(masked_copy_kernel<bf16_t>, dim3(blocks_for(numel)), dim3(256), 0, s,
+        SOL_LAUNCH(masked_copy_kernel<bf16_t>, dim3(blocks_for(numel)), dim3(256), 0, s,
                            (const bf16_t*)dy, (const bf16_t*)y, (bf16_t*)dres, numel);
     else
-        hipLaunchKernelGGL(masked_copy_kernel<float>, dim3(blocks_for(numel)), dim3(256), 0, s, (const float*)dy,
+        SOL_LAUNCH(masked_copy_kernel<float>, dim3(blocks_for(numel)), dim3(256), 0, s, (const float*)dy,
                            (const float*)y, (float*)dres, numel);
     return hipGetLastError();
 }
@@ -170,10 +170,10 @@ hipError_t launch_l1_grad(int dtype, const void* y, const void* t, void* dy, lon
     if (numel <= 0) return hipSuccess;
     const float inv = (float)(1.0 / (double)numel);
     if (dtype == 1)
-        hipLaunchKernelGGL(l1_grad_kernel<true>, dim3(blocks_for((numel + 7) / 8)), dim3(256), 0, s, y, t, dy, numel, inv,
+        SOL_LAUNCH(l1_grad_kernel<true>, dim3(blocks_for((numel + 7) / 8)), dim3(256), 0, s, y, t, dy, numel, inv,
                            mask_by_y);
     else
-        hipLaunchKernelGGL(l1_grad_kernel<false>, dim3(blocks_for(numel)), dim3(256), 0, s, y, t, dy, numel, inv, mask_by_y);
+        SOL_LAUNCH(l1_grad_kernel<false>, dim3(blocks_for(numel)), dim3(256), 0, s, y, t, dy, numel, inv, mask_by_y);
     return hipGetLastError();
 }
 
@@ -221,13 +221,13 @@ hipError_t launch_maxpool(int dtype, const void* x, void* y, int N, int H, int W
     const long long total = (long long)N * Ho * Wo * C;
     if (total <= 0) return hipSuccess;
     if (dtype == 1 && (C & 7) == 0)
-        hipLaunchKernelGGL(maxpool_bf16x8_kernel, dim3(blocks_for(total >> 3)), dim3(256), 0, s, (const bf16_t*)x,
+        SOL_LAUNCH(maxpool_bf16x8_kernel, dim3(blocks_for(total >> 3)), dim3(256), 0, s, (const bf16_t*)x,
                            (bf16_t*)y, N, H, W, C, k, stride, pad, Ho, Wo);
     else if (dtype == 1)
-        hipLaunchKernelGGL(maxpool_kernel<true>, dim3(blocks_for(total)), dim3(256), 0, s, x, y, N, H, W, C, k, stride,
+        SOL_LAUNCH(maxpool_kernel<true>, dim3(blocks_for(total)), dim3(256), 0, s, x, y, N, H, W, C, k, stride,
                            pad, Ho, Wo);
     else
-        hipLaunchKernelGGL(maxpool_kernel<false>, dim3(blocks_for(total)), dim3(256), 0, s, x, y, N, H, W, C, k,
+        SOL_LAUNCH(maxpool_kernel<false>, dim3(blocks_for(total)), dim3(256), 0, s, x, y, N, H, W, C, k,
                            stride, pad, Ho, Wo);
     return hipGetLastError();
 }

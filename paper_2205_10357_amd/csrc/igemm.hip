@@ -288,7 +288,7 @@ static hipError_t launch_tile(const IgemmParams& p, bool vec, bool mask, hipStre
         static std::atomic<size_t> granted{0};     // one per kernel instantiation (the lambda is generic)
         if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), smem, granted); e != hipSuccess)
             return e;
-        hipLaunchKernelGGL(kern, grid, block, smem, stream, p);
+        SOL_LAUNCH(kern, grid, block, smem, stream, p);
         return hipGetLastError();
     };
     if (vec) return mask ? go(igemm_bf16_kernel<BP, BC, WP, WC, true, true>)

@@ -428,7 +428,7 @@ static hipError_t launch_fast_tile(const IgemmParams& p, hipStream_t stream) {
     auto kern = igemm_fast_kernel<BP, BC, WP, WC, NS>;
     static std::atomic<size_t> granted{0};
     if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), smem, granted); e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(p.total_tiles), dim3(256), smem, stream, p);
+    SOL_LAUNCH(kern, dim3(p.total_tiles), dim3(256), smem, stream, p);
     return hipGetLastError();
 }
 

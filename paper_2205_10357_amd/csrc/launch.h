@@ -3,6 +3,8 @@
 
 #include "common.h"
 
+#include <hip/hip_ext.h>
+
 #include <atomic>
 
 namespace sol {
@@ -16,6 +18,25 @@ inline hipError_t ensure_dynamic_lds(const void* kernel, size_t bytes, std::atom
     if (e == hipSuccess) granted.store(bytes, std::memory_order_release);
     return e;
 }
+
+// Launch trace: while a trace is on (sol_trace_start), every kernel launch of the library carries a start and a
+// stop event of its own (the runtime stamps them from the dispatch itself, so the time between them is the
+// kernel's execution time, as a profiler would report it, without a barrier between kernels).  trace_point names
+// the kind of the launches that follow; off, a launch pays one relaxed atomic load.
+extern std::atomic<bool> g_trace_on;
+extern std::atomic<int> g_trace_kind;
+bool trace_take_events(hipStream_t stream, hipEvent_t* start, hipEvent_t* stop);
+inline void trace_point(hipStream_t, int kind) {
+    if (g_trace_on.load(std::memory_order_relaxed)) g_trace_kind.store(kind, std::memory_order_relaxed);
+}
+#define SOL_LAUNCH(kern, grid, block, smem, stream, ...)                                                           \
+    do {                                                                                                           \
+        hipEvent_t sol_ev0_, sol_ev1_;                                                                             \
+        if (sol::g_trace_on.load(std::memory_order_relaxed) && sol::trace_take_events(stream, &sol_ev0_, &sol_ev1_)) \
+            hipExtLaunchKernelGGL(kern, grid, block, smem, stream, sol_ev0_, sol_ev1_, 0, __VA_ARGS__);            \
+        else                                                                                                       \
+            hipLaunchKernelGGL(kern, grid, block, smem, stream, __VA_ARGS__);                                      \
+    } while (0)
 
 struct DirectParams {
     const float* x;

@@ -197,7 +197,7 @@ hipError_t launch_smallc_prepare(const SmallCParams& p, hipStream_t stream) {
     const long long pixels = (long long)p.N * p.H * p.W;
     const int pad_blocks = smallc_pad_blocks(pixels);
     const int pack_blocks = p.wp ? (2 * p.KH * SC_CO * 2 + 255) / 256 : 0;     // no packed weights wanted: pad only
-    hipLaunchKernelGGL(smallc_prepare_kernel, dim3(pad_blocks + pack_blocks), dim3(256), 0, stream, p);
+    SOL_LAUNCH(smallc_prepare_kernel, dim3(pad_blocks + pack_blocks), dim3(256), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -207,7 +207,7 @@ static hipError_t launch_smallc_fwd_kh(const SmallCParams& p, hipStream_t stream
     const long long tiles = (long long)p.N * p.Ho * segs;
     const long long cap = 512;                                 // two workgroups per compute unit
     const int grid = (int)(tiles < cap ? tiles : cap);         // several tiles per workgroup amortise the weight fetch
-    hipLaunchKernelGGL(smallc_fwd_kernel<KH>, dim3(grid), dim3(256), 0, stream, p);
+    SOL_LAUNCH(smallc_fwd_kernel<KH>, dim3(grid), dim3(256), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -422,9 +422,9 @@ size_t smallc_wgrad_partial_bytes(int nparts) { return (size_t)nparts * SC_CO * 
 
 template <int KH>
 static hipError_t launch_smallc_wgrad_kh(const SmallCWgradParams& p, hipStream_t stream) {
-    hipLaunchKernelGGL(smallc_wgrad_kernel<KH>, dim3(p.nparts), dim3(256), 0, stream, p);
+    SOL_LAUNCH(smallc_wgrad_kernel<KH>, dim3(p.nparts), dim3(256), 0, stream, p);
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
-    hipLaunchKernelGGL(smallc_wgrad_reduce_kernel, dim3(SC_CO), dim3(1024), 0, stream, p);
+    SOL_LAUNCH(smallc_wgrad_reduce_kernel, dim3(SC_CO), dim3(1024), 0, stream, p);
     return hipGetLastError();
 }
 

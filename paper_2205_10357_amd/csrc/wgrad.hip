@@ -340,7 +340,7 @@ hipError_t launch_wgrad(const WgradParams& p, bool vec, bool mask, hipStream_t s
         static std::atomic<size_t> granted{0};     // one per kernel instantiation (the lambda is generic)
         if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), smem, granted); e != hipSuccess)
             return e;
-        hipLaunchKernelGGL(kern, grid, block, smem, stream, p);
+        SOL_LAUNCH(kern, grid, block, smem, stream, p);
         return hipGetLastError();
     };
     if (vec) return mask ? go(wgrad_bf16_kernel<true, true>) : go(wgrad_bf16_kernel<true, false>);
@@ -348,8 +348,8 @@ hipError_t launch_wgrad(const WgradParams& p, bool vec, bool mask, hipStream_t s
 }
 
 hipError_t launch_wgrad_reduce(const ReduceParams& p, hipStream_t stream) {
-    if ((p.K & 3) == 0) hipLaunchKernelGGL(wgrad_reduce_kernel<true>, dim3(p.C_out), dim3(256), 0, stream, p);
-    else hipLaunchKernelGGL(wgrad_reduce_kernel<false>, dim3(p.C_out), dim3(256), 0, stream, p);
+    if ((p.K & 3) == 0) SOL_LAUNCH(wgrad_reduce_kernel<true>, dim3(p.C_out), dim3(256), 0, stream, p);
+    else SOL_LAUNCH(wgrad_reduce_kernel<false>, dim3(p.C_out), dim3(256), 0, stream, p);
     return hipGetLastError();
 }
 

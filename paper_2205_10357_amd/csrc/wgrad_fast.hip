@@ -267,7 +267,7 @@ static hipError_t launch_wgf(const WgradParams& p, hipStream_t stream) {
     auto kern = wgrad_fast_kernel<NS, LINEAR>;
     static std::atomic<size_t> granted{0};
     if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), smem, granted); e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(p.tiles_k * p.tiles_c * p.splits + p.pack_blocks), dim3(256), smem, stream, p);
+    SOL_LAUNCH(kern, dim3(p.tiles_k * p.tiles_c * p.splits + p.pack_blocks), dim3(256), smem, stream, p);
     return hipGetLastError();
 }
 

@@ -125,6 +125,7 @@ class Sequencer:
         self.ws = torch.empty((max(ws_bytes, 256),), dtype=torch.uint8, device=self.device)
         self._side: Optional[torch.cuda.Stream] = None
         self._ws_side: Optional[torch.Tensor] = None      # workspace of the second backward lane
+        self._prepared: Optional[B.Sequence] = None       # the step as a prepared sequence of the library
         self.grads: Dict[int, Dict[str, torch.Tensor]] = {}
         self.dact: Dict[int, torch.Tensor] = {}
         self.target: Optional[torch.Tensor] = None
@@ -263,6 +264,38 @@ class Sequencer:
             self.step(lanes=lanes)
         self.graph = graph
         return graph
+
+    def prepared(self) -> "B.Sequence":
+        """The whole step (forward, loss gradient, one-lane backward) recorded once as a prepared sequence of
+        the library: running it issues every launch of the step from native code, in the order ``step`` uses."""
+        if self._prepared is None:
+            q = B.Sequence()
+            for o in self.ops:
+                if o.op == "conv":
+                    p = self.params[o.layer]
+                    q.add_fwd(self.desc[o.layer], self.act[o.inp], p["W"], p["scale"], p["shift"],
+                              self.act[o.res] if o.res is not None else None, self.act[o.out], self.ws, None, o.layer)
+                else:
+                    c, h, w = self.shapes[o.inp]
+                    q.add_maxpool(self.sol_dtype, self.act[o.inp], self.act[o.out], self.wl.n, h, w, c, o.k, o.stride,
+                                  o.pad, -1)
+            self._prepared_fwd = len(q)
+            if self.wl.train:
+                last_op = self.ops[-1]
+                y = self.act[last_op.out]
+                q.add_l1_loss_grad(self.sol_dtype, y, self.target, self.dact[last_op.out], y.numel(),
+                                   bool(getattr(last_op, "relu", False)), -2)
+                for c in self._bwd_calls:
+                    o = c["op"]
+                    p, g = self.params[o.layer], self.grads[o.layer]
+                    q.add_bwd(c["desc"], c["dy"], self.act[o.inp], p["W"], None, c["dx"], g["dW"], g["dscale"],
+                              g["dshift"], p["scale"], None, c["addend"], None, c["dx_mask"], self.ws, None, o.layer)
+            self._prepared = q
+        return self._prepared
+
+    def step_prepared(self, stream=None) -> None:
+        """``step(lanes=1)`` through the prepared sequence: one library call for the whole step."""
+        self.prepared().run(stream=stream if stream is not None else torch.cuda.current_stream(self.device))
 
     def step(self, stream=None, lanes: int = 1) -> None:
         """One pass of the whole path: forward, and for training the loss gradient and backward."""

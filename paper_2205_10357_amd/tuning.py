@@ -113,6 +113,7 @@ def tune(seq: Sequencer, iters: int = 20, margin: float = 0.03) -> Dict[str, Dic
                 if need > seq.ws.numel():
                     torch.cuda.synchronize()
                     seq.ws = torch.empty((need,), dtype=torch.uint8, device=seq.device)
+                    seq._prepared = None          # a prepared step recorded the old workspace
             tiles = -(-(d.KH * d.KW * d.C_in) // 128) * -(-d.C_out // 128)
             splits = sorted({max(1, -(-t // tiles)) for t in WGRAD_TARGETS})
             entry["wgrad"] = _best(c["desc"], B.SOL_PLAN_WGRAD, [(-1, s, k) for k in splits for s in (2, 3)], wgrad,

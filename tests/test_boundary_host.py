@@ -137,3 +137,34 @@ def test_launch_plans_are_a_host_side_table():
         assert B.sol_block_get_plan(d, B.SOL_PLAN_FWD) == (-1, 0, 0)
     finally:
         B.sol_clear_plans()
+
+
+def test_prepared_sequence_records_on_the_host_and_reports_the_failing_call():
+    """Recording touches no device and validates nothing; running stops at the first call whose own checks
+    fail and returns that status (here: before any HIP call, so this runs without a GPU)."""
+    q = B.Sequence()
+    assert len(q) == 0
+    bad = B.BlockDesc(1, 8, 8, 8, 8, 3, 3, 0, 1, B.SOL_BF16, 0)                # stride 0
+    ok = B.BlockDesc(1, 8, 8, 8, 8, 3, 3, 1, 1, B.SOL_BF16, 0)
+    q.add_fwd(ok, None, 4096, 4096, 4096, None, 4096, None, 0, tag=1)          # x is NULL
+    q.add_fwd(bad, 4096, 4096, 4096, 4096, None, 4096, None, 0, tag=2)
+    q.add_l1_loss_grad(B.SOL_BF16, 4096, 4096, 4096, 0, False, tag=3)          # numel 0
+    q.add_bwd(ok, 4096, 4096, 4096, None, 4096, 4096, 4096, 4096, 4096, ws=None, ws_bytes=0, tag=4)   # no workspace
+    assert len(q) == 4
+    assert q.run(0, 1, stream=0, check=False) == -1
+    assert q.run(1, 1, stream=0, check=False) == -2
+    assert q.run(2, 1, stream=0, check=False) == -2
+    assert q.run(3, 1, stream=0, check=False) == -5
+    assert q.run(0, 4, stream=0, check=False) == -1                            # stops at the first
+    assert q.run(0, 0, stream=0, check=False) == 0
+    assert q.run(3, 2, stream=0, check=False) == -2                            # range beyond the recorded calls
+    assert q.run(-1, 1, stream=0, check=False) == -2
+
+
+def test_trace_kind_names_and_stop_without_start():
+    names = {B.sol_trace_kind_name(k) for k in range(0, 15)}
+    assert len(names) == 15 and "unknown" not in names
+    assert B.sol_trace_kind_name(99) == "unknown"
+    import ctypes as C
+    n = C.c_int32(7)
+    assert B.lib().sol_trace_stop(None, 0, C.byref(n)) == -4                  # no trace is running

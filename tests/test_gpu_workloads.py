@@ -370,3 +370,45 @@ def test_tuned_plans_change_speed_only():
         assert all(torch.equal(seq2.grads[k]["dW"], dw0[k]) for k in dw0)
     finally:
         B.sol_clear_plans()
+
+
+def test_prepared_step_and_launch_trace():
+    """The step recorded as a prepared sequence of the library gives the eager step's bits, and a launch trace
+    of it lists the 13 launches of the bottleneck step by kind and layer, each with a plausible time."""
+    w = wl.bottleneck14_bf16(n=8)
+    seq = runner.Sequencer(w, "cuda:0")
+    seq.step()
+    torch.cuda.synchronize()
+    ref = {k: v.clone() for k, v in seq.dact.items()}
+    ref_g = {k: {n: t.clone() for n, t in v.items()} for k, v in seq.grads.items()}
+    ref_y = seq.act[w.ops[-1].out].clone()
+    for t in list(seq.dact.values()) + [t for v in seq.grads.values() for t in v.values()]:
+        t.fill_(5.0)
+    assert len(seq.prepared()) == 7
+    B.sol_trace_start(256)
+    for _ in range(3):
+        seq.step_prepared()
+    trace = B.sol_trace_stop(256)
+    torch.cuda.synchronize()
+    assert torch.equal(seq.act[w.ops[-1].out], ref_y)
+    for k, v in ref.items():
+        if any(c["dx"] is seq.dact[k] for c in seq._bwd_calls) or k == w.ops[-1].out:
+            assert torch.equal(seq.dact[k], v), k
+    for k, v in ref_g.items():
+        for n, t in v.items():
+            assert torch.equal(seq.grads[k][n], t), (k, n)
+    assert len(trace) == 3 * 13
+    kinds = [B.sol_trace_kind_name(k) for k, _, _, _ in trace[:13]]
+    print("[trace]", [(B.sol_trace_kind_name(k), tag, round(us, 1), round(at, 1)) for k, tag, us, at in trace[13:26]], flush=True)
+    assert kinds.count("implicit GEMM (pipelined)") == 6 and kinds.count("weight-gradient GEMM (pipelined)") == 3
+    assert kinds.count("split reduction") == 3 and kinds.count("L1-loss gradient") == 1
+    assert [tag for _, tag, _, _ in trace[:13]] == [0, 1, 2, -2, 2, 2, 2, 1, 1, 1, 0, 0, 0]
+    assert all(0.5 < us < 5000 for _, _, us, _ in trace)
+    starts = [at for _, _, _, at in trace]
+    assert starts[0] == 0 and all(b > a for a, b in zip(starts, starts[1:]))          # one stream: launches in order
+    # tracing is off again: nothing is recorded, a second stop is refused
+    seq.step_prepared()
+    torch.cuda.synchronize()
+    import ctypes as C
+    n = C.c_int32(0)
+    assert B.lib().sol_trace_stop(None, 0, C.byref(n)) == -4
