@@ -141,9 +141,8 @@ SOL_API size_t sol_block_bwd_noalloc_limit(void);
 
 /* Bytes of caller-provided scratch the given pass needs for this descriptor (0 if the
  * descriptor is invalid: the pass itself then reports the error).  The answer depends on every
- * field of the descriptor, flags included (a backward pass that masks dy itself uses another
- * weight-gradient kernel and another split than one that gets dy already masked): ask with the
- * descriptor the call will carry. */
+ * field of the descriptor, flags included (a backward pass that masks dy itself keeps the masked
+ * gradient in the workspace): ask with the descriptor the call will carry. */
 SOL_API size_t sol_block_workspace_bytes(const sol_block_desc* desc, int pass);
 
 /*

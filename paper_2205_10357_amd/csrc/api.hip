@@ -56,12 +56,12 @@ inline void clear_stale_error() { (void)hipGetLastError(); }
 // backward call used to make some fifteen of them.
 enum Knob {
     K_IGEMM_TILE, K_IGEMM_FAST, K_FAST_TILE, K_FAST_SHORTK, K_FAST_MANY, K_FAST_STAGES, K_WGRAD_SPLITS, K_WGRAD_TARGET,
-    K_SMALLC, K_FILL_UNTOUCHED, K_WGRAD_FAST, K_PACK_FUSED, K_WGRAD_STAGES, K_WGRAD_TICKET, K_COUNT
+    K_SMALLC, K_FILL_UNTOUCHED, K_WGRAD_FAST, K_PACK_FUSED, K_WGRAD_STAGES, K_WGRAD_TICKET, K_PREMASK, K_COUNT
 };
 const char* const kKnobNames[K_COUNT] = {
     "SOL_IGEMM_TILE", "SOL_IGEMM_FAST", "SOL_FAST_TILE", "SOL_FAST_SHORTK", "SOL_FAST_MANY", "SOL_FAST_STAGES",
     "SOL_WGRAD_SPLITS", "SOL_WGRAD_TARGET", "SOL_SMALLC", "SOL_FILL_UNTOUCHED", "SOL_WGRAD_FAST", "SOL_PACK_FUSED",
-    "SOL_WGRAD_STAGES", "SOL_WGRAD_TICKET"};
+    "SOL_WGRAD_STAGES", "SOL_WGRAD_TICKET", "SOL_PREMASK"};
 constexpr int kKnobUnset = INT32_MIN;
 std::atomic<int> g_knobs[K_COUNT];
 std::atomic<bool> g_knobs_loaded{false};
@@ -197,7 +197,16 @@ struct BwdPlan {
     bool smallc;
     int sc_parts;
     size_t sc_xp_off, sc_part_off;
+    // a block that masks dy itself (SOL_RELU): the masked gradient, written once by an element-wise launch so that
+    // both gradient GEMMs take the pipelined kernels (which gather their operands without looking at y)
+    bool premask;
+    size_t gmask_off;
 };
+
+// channel counts the 16-byte operand pieces of the bf16 kernels need
+inline bool bf16_vector_shape(const sol_block_desc* d) {
+    return d->dtype == SOL_BF16 && (d->C_in % 8) == 0 && (d->C_out % 8) == 0;
+}
 
 BwdPlan plan_bwd(const sol_block_desc* d, const Geometry& g) {
     BwdPlan b{};
@@ -242,6 +251,12 @@ BwdPlan plan_bwd(const sol_block_desc* d, const Geometry& g) {
         b.sc_xp_off = b.total;
         b.sc_part_off = b.sc_xp_off + align_up(smallc_padded_image_bytes(d->N, d->H, d->W));
         b.total = b.sc_part_off + align_up(smallc_wgrad_partial_bytes(b.sc_parts));
+    }
+    b.premask = (d->flags & SOL_RELU) != 0 && d->dtype == SOL_BF16 && (bf16_vector_shape(d) || b.smallc) &&
+                knob(K_PREMASK, 1) != 0;
+    if (b.premask) {
+        b.gmask_off = b.total;
+        b.total += align_up((size_t)g.y_elems * 2);
     }
     return b;
 }
@@ -315,13 +330,13 @@ int fwd_bf16(const sol_block_desc* d, const Geometry& g, const void* x, const vo
     return run_igemm(p, rows, false, installed_plan(d, SOL_PLAN_FWD), stream);
 }
 
-int dgrad_bf16(const sol_block_desc* d, const Geometry& g, const void* dy, const void* y, const bf16_t* wpack,
+int dgrad_bf16(const sol_block_desc* d, const Geometry& g, const void* dy, const void* ymask, const bf16_t* wpack,
                void* dx, const void* addend, const void* addend_mask, const void* dx_mask, hipStream_t stream) {
     const int s = d->stride;
     IgemmParams p{};
-    const bool relu = (d->flags & SOL_RELU) != 0;
+    const bool relu = ymask != nullptr;          // mask dy by y > 0 while gathering it
     p.src = (const bf16_t*)dy;
-    p.src_mask = relu ? (const bf16_t*)y : nullptr;
+    p.src_mask = (const bf16_t*)ymask;
     p.wmat = wpack;
     p.out = (bf16_t*)dx;
     p.scale = nullptr;
@@ -486,7 +501,7 @@ static int bwd_common(const sol_block_desc* desc, const void* dy, const void* x,
                       void* hip_stream) {
     Geometry g;
     if (int e = check_desc(desc, &g); e != SOL_OK) return e;
-    const bool relu = (desc->flags & SOL_RELU) != 0;
+    bool relu = (desc->flags & SOL_RELU) != 0;
     if (!dy || !x || !W || !scale) return SOL_ERR_NULL;
     if (dW ? (!dscale || !dshift) : (dscale || dshift)) return SOL_ERR_NULL;   // the three come together
     if (!dW && !dx && !dres) return SOL_ERR_NULL;                              // nothing to compute
@@ -508,6 +523,17 @@ static int bwd_common(const sol_block_desc* desc, const void* dy, const void* x,
     unsigned char* wsb = (unsigned char*)ws;
     float* partial = (float*)(wsb + plan.part_off);
     float* dshift_partial = (float*)(wsb + plan.dshift_off);
+    // A block that masks dy itself: write g = (y > 0 ? dy : 0) once (into dres when the caller wants it anyway) and
+    // run everything below on g as a block without ReLU.
+    bool dres_done = false;
+    if (plan.premask) {
+        void* gbuf = dres ? dres : (void*)(wsb + plan.gmask_off);
+        trace_point(stream, SOL_TRACE_MASKED_COPY);
+        if (launch_masked_copy(desc->dtype, dy, y, gbuf, g.y_elems, stream) != hipSuccess) return SOL_ERR_LAUNCH;
+        dy = gbuf;
+        relu = false;
+        dres_done = dres != nullptr;
+    }
     const void* ymask = relu ? y : nullptr;
 
     auto direct_params = [&]() {
@@ -531,7 +557,7 @@ static int bwd_common(const sol_block_desc* desc, const void* dy, const void* x,
 
     // The re-pack of the weights for the data gradient rides along with the weight-gradient launch (as extra
     // workgroups) when one call computes both branches with the pipelined kernels; else it is a launch of its own.
-    const bool bf16_vec = desc->dtype == SOL_BF16 && (desc->C_in % 8) == 0 && (desc->C_out % 8) == 0;
+    const bool bf16_vec = bf16_vector_shape(desc);
     const bool wgrad_pipelined = bf16_vec && !relu && knob(K_WGRAD_FAST, 1) != 0;
     PackParams pk{(const bf16_t*)W, scale, (bf16_t*)(wsb + plan.wpack_off), desc->C_in, desc->C_out, desc->KH,
                   desc->KW, desc->stride, desc->pad};
@@ -539,14 +565,15 @@ static int bwd_common(const sol_block_desc* desc, const void* dy, const void* x,
 
     // ---- data branch: shortcut gradient, weight re-pack, data-gradient GEMM ----
     auto data_branch = [&](hipStream_t st) -> int {
-        if (dres) trace_point(st, SOL_TRACE_MASKED_COPY);
-        if (dres && launch_masked_copy(desc->dtype, dy, ymask, dres, g.y_elems, st) != hipSuccess)
-            return SOL_ERR_LAUNCH;
+        if (dres && !dres_done) {
+            trace_point(st, SOL_TRACE_MASKED_COPY);
+            if (launch_masked_copy(desc->dtype, dy, ymask, dres, g.y_elems, st) != hipSuccess) return SOL_ERR_LAUNCH;
+        }
         if (!dx) return SOL_OK;
         if (desc->dtype == SOL_BF16) {
             if (!pack_rides) trace_point(st, SOL_TRACE_PACK);
             if (!pack_rides && launch_pack_dgrad_weights(pk, st) != hipSuccess) return SOL_ERR_LAUNCH;
-            return dgrad_bf16(desc, g, dy, y, pk.out, dx, dx_addend, dx_addend_mask, dx_mask, st);
+            return dgrad_bf16(desc, g, dy, ymask, pk.out, dx, dx_addend, dx_addend_mask, dx_mask, st);
         }
         DirectParams p = direct_params();
         trace_point(st, SOL_TRACE_DIRECT);

@@ -45,6 +45,19 @@ __global__ __launch_bounds__(256) void masked_copy_kernel(const T* dy, const T* 
     }
 }
 
+// bf16, 8 elements (16 bytes) per thread; the last thread finishes a ragged tail element by element
+__global__ __launch_bounds__(256) void masked_copy_bf16x8_kernel(const bf16_t* dy, const bf16_t* y, bf16_t* dres,
+                                                                 long long numel) {
+    const long long i8 = ((long long)blockIdx.x * 256 + threadIdx.x) * 8;
+    if (i8 >= numel) return;
+    if (i8 + 8 <= numel) {
+        const uintx4 g = *reinterpret_cast<const uintx4*>(dy + i8);
+        *reinterpret_cast<uintx4*>(dres + i8) = y ? mask_where_positive(g, *reinterpret_cast<const uintx4*>(y + i8)) : g;
+    } else {
+        for (long long i = i8; i < numel; ++i) dres[i] = (!y || (short)y[i] > 0) ? dy[i] : (bf16_t)0;
+    }
+}
+
 // dy = sign(y - t) / numel, optionally zero where y <= 0.  bf16: 8 elements (16 bytes) per thread.
 template <bool BF16>
 __global__ __launch_bounds__(256) void l1_grad_kernel(const void* yv, const void* tv, void* dyv, long long numel,
@@ -157,8 +170,8 @@ hipError_t launch_pack_dgrad_weights(const PackParams& p, hipStream_t s) {
 hipError_t launch_masked_copy(int dtype, const void* dy, const void* y, void* dres, long long numel, hipStream_t s) {
     if (numel <= 0) return hipSuccess;
     if (dtype == 1)
-        SOL_LAUNCH(masked_copy_kernel<bf16_t>, dim3(blocks_for(numel)), dim3(256), 0, s,
-                           (const bf16_t*)dy, (const bf16_t*)y, (bf16_t*)dres, numel);
+        SOL_LAUNCH(masked_copy_bf16x8_kernel, dim3(blocks_for((numel + 7) / 8)), dim3(256), 0, s,
+                   (const bf16_t*)dy, (const bf16_t*)y, (bf16_t*)dres, numel);
     else
         SOL_LAUNCH(masked_copy_kernel<float>, dim3(blocks_for(numel)), dim3(256), 0, s, (const float*)dy,
                            (const float*)y, (float*)dres, numel);

@@ -163,6 +163,23 @@ def test_bf16_every_tile_shape(tile, sol_env):
     show(f"tile{tile}", pu.check_block(case, got))
 
 
+@pytest.mark.parametrize("premask", [0, 1])
+@pytest.mark.parametrize("want_dres", [False, True])
+@pytest.mark.parametrize("shape", [
+    dict(N=2, H=14, W=14, C_in=64, C_out=128, K=3, stride=1, pad=1, res=True),
+    dict(N=2, H=15, W=13, C_in=128, C_out=64, K=1, stride=2, pad=0),
+])
+def test_block_that_masks_its_own_gradient(shape, want_dres, premask, sol_env):
+    """sol_block_bwd with SOL_RELU and y, the call as the interface states it.  By default the library writes the
+    masked gradient once (into dres when the caller asks for it, else into the workspace) and runs both gradient
+    GEMMs with the pipelined kernels; SOL_PREMASK=0 keeps the mask inside the general kernels' operand staging.
+    Same checks either way, dres bit-exact."""
+    sol_env("SOL_PREMASK", premask)
+    case = pu.make_case(91, **shape)
+    got = pu.gpu_block(case, want_dres=want_dres)
+    show(f"own mask premask={premask} dres={want_dres} {shape}", pu.check_block(case, got))
+
+
 @pytest.mark.parametrize("splits", [1, 3, 50])
 def test_bf16_wgrad_split_counts(splits, sol_env):
     sol_env("SOL_WGRAD_SPLITS", splits)
