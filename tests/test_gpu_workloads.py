@@ -316,6 +316,46 @@ def test_inference_arena_gives_the_retained_run_bit_for_bit(size):
         assert torch.equal(out, ref)
 
 
+@pytest.mark.parametrize("size", ["small", "full"])
+def test_inference_graph_replays_match_eager_and_checker(size):
+    """The inference version of the schedule (nothing retained, one activation arena) captured as a HIP graph:
+    every replay, with eager work and synchronisations in between, gives the eager run's bits; the eager run is
+    compared with the CPU checker on sampled outputs of the network's last layer (teacher-forced on the
+    retained run of the same schedule)."""
+    w = wl.resnet50_infer_bf16(n=2, hw=64) if size == "small" else wl.resnet50_infer_bf16()
+    seq = runner.Sequencer(w, "cuda:0")
+    assert not seq.retain
+    ref = seq.forward().clone()
+    torch.cuda.synchronize()
+    g = seq.capture(lanes=1)
+    out = seq.act[w.ops[-1].out]
+    for it in range(3):
+        seq.arena.fill_(77)                  # eager work between the replays: the arena is dirty
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref), it
+    seq.step_prepared()                      # the prepared sequence issues the same launches
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref)
+    del seq, g
+    # the last block against the checker, fed with the tensors a retained run stored
+    kept = runner.Sequencer(w, "cuda:0", retain_activations=True)
+    assert torch.equal(kept.forward(), ref)
+    torch.cuda.synchronize()
+    o = w.conv_blocks()[-1]
+    images = [0, w.n - 1]
+    d = desc_of(kept, o, len(images))
+    p = w.params[o.layer]
+    rng = np.random.default_rng(17)
+    pts = rand_points(rng, (len(images), o.c_out, d.Ho, d.Wo), 300)
+    v, y, mag = orc.fwd_points(d, host(kept.act[o.inp], images), p["W"], p["scale"], p["shift"],
+                               host(kept.act[o.res], images) if o.res is not None else None, pts)
+    got = host(ref, images)[tuple(pts.T)]
+    assert rel(got, y) < TOL
+    pu.assert_elementwise_bf16("y (graph)", got, y, mag)
+
+
 def test_plan_sweep_covers_strided_and_projection_layers():
     """The sweep on the stage-2 topology (stride-2 3x3, stride-2 1x1 projection, identity blocks): every distinct
     layer shape is timed for the kernels that serve it, installed plans are valid table entries, and the chain
@@ -397,12 +437,13 @@ def test_prepared_step_and_launch_trace():
     for k, v in ref_g.items():
         for n, t in v.items():
             assert torch.equal(seq.grads[k][n], t), (k, n)
-    assert len(trace) == 3 * 13
-    kinds = [B.sol_trace_kind_name(k) for k, _, _, _ in trace[:13]]
-    print("[trace]", [(B.sol_trace_kind_name(k), tag, round(us, 1), round(at, 1)) for k, tag, us, at in trace[13:26]], flush=True)
+    per_step = 13
+    assert len(trace) == 3 * per_step
+    kinds = [B.sol_trace_kind_name(k) for k, _, _, _ in trace[:per_step]]
+    print("[trace]", [(B.sol_trace_kind_name(k), tag, round(us, 1), round(at, 1)) for k, tag, us, at in trace[per_step:2 * per_step]], flush=True)
     assert kinds.count("implicit GEMM (pipelined)") == 6 and kinds.count("weight-gradient GEMM (pipelined)") == 3
     assert kinds.count("split reduction") == 3 and kinds.count("L1-loss gradient") == 1
-    assert [tag for _, tag, _, _ in trace[:13]] == [0, 1, 2, -2, 2, 2, 2, 1, 1, 1, 0, 0, 0]
+    assert [tag for _, tag, _, _ in trace[:per_step]] == [0, 1, 2, -2, 2, 2, 2, 1, 1, 1, 0, 0, 0]
     assert all(0.5 < us < 5000 for _, _, us, _ in trace)
     starts = [at for _, _, _, at in trace]
     assert starts[0] == 0 and all(b > a for a, b in zip(starts, starts[1:]))          # one stream: launches in order
