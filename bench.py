@@ -152,6 +152,8 @@ def per_launch_table(trace, wl, seq, B, steps):
     """Median time per position of the step and the roofline that binds each launch."""
     per_step = len(trace) // steps
     assert per_step * steps == len(trace), (len(trace), steps)
+    assert all(trace[s * per_step + i][:2] == trace[i][:2] for s in range(steps) for i in range(per_step)), \
+        "the traced steps differ in their launches"
     costs = launch_costs(wl, seq, B)
     names = {b.layer: b.name for b in wl.conv_blocks()}
     rows = []
@@ -251,7 +253,7 @@ def main():
 
     # ---- every launch of the step, timed with events on the launch stream (the library's launch trace) ----
     trace_steps = max(20, min(100, args.steps))
-    points = trace_steps * (3 * len(wl.ops) + 4)
+    points = trace_steps * (8 * len(wl.ops) + 8)       # more than any schedule launches (a backward call: at most 7)
     B.sol_trace_start(points)
     for _ in range(trace_steps):
         seq.step_prepared(stream)
