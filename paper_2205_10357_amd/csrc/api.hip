@@ -127,7 +127,18 @@ int pick_igemm_tile(const long long* class_rows, int ncls, int Nc) {
 int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& tuned, hipStream_t stream) {
     bool few_taps = true;                       // the pipelined kernel keeps one validity bit per tap
     for (int c = 0; c < p.ncls; ++c) few_taps = few_taps && p.cls[c].Th * p.cls[c].Tw <= 32;
-    const bool fast_ok = !mask && few_taps && (p.Cs % 64) == 0 && (p.Nc % 8) == 0 &&
+    // the pipelined kernel starts its buffer descriptor a few image rows before the gathered tensor (the reach of the
+    // taps around a pixel); tensor plus that reach must stay below 2^32 bytes
+    long long reach = 0;
+    for (int c = 0; c < p.ncls; ++c) {
+        const RowClass& rc = p.cls[c];
+        const long long first = ((long long)rc.h_off * p.Ws + rc.w_off) * p.Cs * 2;
+        const long long last = (((long long)(rc.Th - 1) * p.Ws + (rc.Tw - 1)) * rc.tap_step) * p.Cs * 2;
+        const long long m = (first < 0 ? -first : 0) + (last < 0 ? -last : 0);
+        if (m > reach) reach = m;
+    }
+    const bool addressable = (long long)p.src_bytes + reach <= 0xffffffffLL && reach <= 0x7fffffffLL;
+    const bool fast_ok = !mask && few_taps && addressable && (p.Cs % 64) == 0 && (p.Nc % 8) == 0 &&
                          knob(K_IGEMM_FAST, 1) != 0;
     int bp, bc, tile = 0, stages = 0;
     bool many_tiles = false;

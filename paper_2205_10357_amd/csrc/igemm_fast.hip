@@ -96,7 +96,17 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
     // Copies go through buffer descriptors: per row a loop-invariant byte offset, per slice one
     // wave-uniform tap / channel offset; a lane whose tap falls outside the image (or whose row
     // does not exist) gets an out-of-range offset and reads zeros.
-    const buffer_rsrc_t src_rs = make_buffer_rsrc(p.src, p.src_bytes);
+    // The per-slice part of a pixel copy's address (tap and channel-slice offset) is wave-uniform and travels in the
+    // instruction's scalar offset, which must not be negative; the vector offset must stay inside the descriptor for
+    // every valid (row, tap).  Both hold once the descriptor starts `margin` bytes before the tensor: margin = how far
+    // tap 0 of the first pixel lies before the tensor (padding) plus how far the last tap lies before tap 0 (data
+    // gradient: taps walk backwards).  Only addresses inside the tensor are ever dereferenced: an invalid tap gets an
+    // out-of-range vector offset.
+    const int tap0_first = ((rc.h_off * p.Ws + rc.w_off) * p.Cs) * 2;
+    const int tap_last = ((((rc.Th - 1) * p.Ws + (rc.Tw - 1)) * rc.tap_step) * p.Cs) * 2;
+    const int delta_min = tap_last < 0 ? tap_last : 0;
+    const unsigned margin = (unsigned)((tap0_first < 0 ? -tap0_first : 0) - delta_min);
+    const buffer_rsrc_t src_rs = make_buffer_rsrc(reinterpret_cast<const char*>(p.src) - margin, p.src_bytes + margin);
     const buffer_rsrc_t w_rs = make_buffer_rsrc(wmat, (unsigned)(K * p.Nc * 2));
     const int j8 = lane >> 3, pc = lane & 7;
     unsigned rowb[LP];                     // byte offset of (row, tap 0, logical chunk), modulo 2^32
@@ -149,35 +159,52 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
         wrowb[i] = c < p.Nc ? (unsigned)(c * (int)K + cl * 8) * 2u : kOutOfRange;
     }
 
-    // running position of the next slice to request; a slice is requested in four parts so that
-    // the copies can be issued between the MFMAs of the slice being multiplied
-    int q_kt = 0, q_cs = 0, q_th = 0, q_tw = 0, q_tap = 0;
-    auto request_part = [&](int part, int nparts) {
-        uintx4* st = lds + (q_kt % NS) * STAGE;
-        const unsigned delta = (unsigned)((((q_th * p.Ws + q_tw) * rc.tap_step) * p.Cs + q_cs * 64) * 2);
+    // Requests are issued slice by slice in ring order; a slice is requested in parts so that the copies can be issued
+    // between the MFMAs of the slice being multiplied.  Everything a request needs is ready before it starts: the
+    // scalar offsets of the next slice (pixel and weight operand) and, after a change of tap, the vector offsets are
+    // computed right after the last copy of the previous request, under the MFMAs -- not between the barrier and the
+    // first copy, where the whole wave would wait for a chain of dependent scalar instructions.  Within a tap a slice
+    // costs two scalar adds.
+    int q_cs = 0, q_th = 0, q_tw = 0, q_tap = 0, q_stage = 0;
+    unsigned s_pix = (unsigned)(-delta_min);   // scalar offset of the pixel copies: tap + channel slice, biased to be >= 0
+    unsigned s_w = 0u;                         // scalar offset of the weight copies: 128 bytes per slice
+    unsigned voff[LP];                         // vector offset of this thread's pixel copies for the current tap:
+#pragma unroll                                 // all-ones where the tap lies outside the image
+    for (int i = 0; i < LP; ++i) voff[i] = (rowb[i] + margin + (unsigned)delta_min) | (unsigned)__builtin_amdgcn_sbfe((int)badtap[i], 0, 1);
+    auto request_part = [&](int stage, int part, int nparts) {
+        uintx4* st = lds + stage * STAGE;
 #pragma unroll
         for (int i = 0; i < LPS; ++i) {
             if (i < (part * LPS) / nparts || i >= ((part + 1) * LPS) / nparts) continue;
             if (i < LP) {
-                // all-ones when the tap is invalid for this row, else zero
-                const unsigned inval = (unsigned)((int)(badtap[i] << (31 - q_tap)) >> 31);
-                dma16_buf_to_lds(src_rs, (rowb[i] + delta) | inval, 0u, st + (32 * i + 8 * wave) * 8);
+                dma16_buf_to_lds(src_rs, voff[i], s_pix, st + (32 * i + 8 * wave) * 8);
             } else {
                 const int iw = i - LP;
-                dma16_buf_to_lds(w_rs, wrowb[iw], (unsigned)(q_kt * 128), st + BP * 8 + (32 * iw + 8 * wave) * 8);
+                dma16_buf_to_lds(w_rs, wrowb[iw], s_w, st + BP * 8 + (32 * iw + 8 * wave) * 8);
             }
         }
         if (part == nparts - 1) {
-            ++q_kt;
-            if (++q_cs == cpt) {
+            s_w += 128u;
+            if (__builtin_expect(++q_cs == cpt, 0)) {      // next tap (never taken again by a 1x1 layer)
                 q_cs = 0;
                 ++q_tap;
                 if (++q_tw == rc.Tw) {
                     q_tw = 0;
                     ++q_th;
                 }
+                s_pix = (unsigned)((((q_th * p.Ws + q_tw) * rc.tap_step) * p.Cs) * 2 - delta_min);
+#pragma unroll
+                for (int i = 0; i < LP; ++i)
+                    voff[i] = (rowb[i] + margin + (unsigned)delta_min) | (unsigned)__builtin_amdgcn_sbfe((int)badtap[i], q_tap & 31, 1);
+            } else {
+                s_pix += 128u;
             }
         }
+    };
+    // for the loops that do not know the ring stage at compile time
+    auto request_part_rt = [&](int part, int nparts) {
+        request_part(q_stage, part, nparts);
+        if (part == nparts - 1) q_stage = q_stage + 1 == NS ? 0 : q_stage + 1;
     };
 
     const int wp = wave % WP, wc = wave / WP;
@@ -193,7 +220,7 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
     for (int s = 0; s < NS - 1; ++s)
         if (s < nk) {
 #pragma unroll
-            for (int part = 0; part < 4; ++part) request_part(part, 4);
+            for (int part = 0; part < 4; ++part) request_part_rt(part, 4);
         }
 
     // LDS chunk index (inside a stage) of this lane's operand fragment for each of the 4 steps
@@ -237,11 +264,21 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
         // issued after the barrier in three parts between the MFMA groups.  The instruction order
         // "fragments of the next step, copies, MFMAs of this step" is pinned with scheduling-group
         // barriers: left alone, the scheduler sinks the LDS reads below the MFMAs that precede their use.
-        auto slice = [&](int kt, auto next_tag, auto more_tag) {
+        // The ring stage of a slice is a compile-time constant (the loop below advances NS slices per iteration), so the
+        // stage's base is an immediate of the fragment reads instead of a vector add per read: with one wave per SIMD
+        // the in-order issue of that wave is what bounds the loop, and the ~16 address adds per slice were ~9 % of it.
+        // (Stages beyond the 64 KB reach of the immediate cost one hoisted address register per fragment; the
+        // 256 x 128 tile has none to spare and keeps the stage in a register.)
+        auto slice = [&](auto stage, auto next_tag, auto more_tag) {
+            const int S = stage;                               // slice kt lives in ring stage S = kt % NS
             constexpr bool NEXT = decltype(next_tag)::value;   // slice kt+1 exists
             constexpr bool MORE = decltype(more_tag)::value;   // slice kt+NS-1 exists and is requested here
-            const uintx4* st = lds + (kt % NS) * STAGE;
-            const uintx4* stn = lds + ((kt + 1) % NS) * STAGE;
+            const uintx4* st = lds + S * STAGE;
+            const uintx4* stn = lds + ((S + 1) % NS) * STAGE;
+            auto request = [&](int part) {                     // slice kt+NS-1 goes where slice kt-1 was
+                if constexpr (std::is_same_v<decltype(stage), int>) request_part_rt(part, 3);
+                else request_part((S + NS - 1) % NS, part, 3);
+            };
             read_frags(1, st, 1);
             multiply(0);
             __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);
@@ -254,16 +291,16 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
                                                 : 0x0f70);
                 wg_barrier();
             }
-            if constexpr (MORE) request_part(0, 3);
+            if constexpr (MORE) request(0);
             multiply(1);
             fast_pin_copies_between_mfmas<MORE ? LPS / 3 : 0, TC * TP>();
             read_frags(1, st, 3);
-            if constexpr (MORE) request_part(1, 3);
+            if constexpr (MORE) request(1);
             multiply(0);
             __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);
             fast_pin_copies_between_mfmas<MORE ? (2 * LPS) / 3 - LPS / 3 : 0, TC * TP>();
             if constexpr (NEXT) read_frags(0, stn, 0);
-            if constexpr (MORE) request_part(2, 3);
+            if constexpr (MORE) request(2);
             multiply(1);
             if constexpr (NEXT) __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);
             fast_pin_copies_between_mfmas<MORE ? LPS - (2 * LPS) / 3 : 0, TC * TP>();
@@ -275,10 +312,41 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
         wg_barrier();
         if (nk > 0) {                // a row class without taps (strided data gradient) has nothing to multiply
             read_frags(0, lds, 0);
+            // R slices starting at a multiple of NS, written out: slice I sits in stage I % NS, has a successor
+            // unless it is the last, and requests slice I + NS - 1 if that exists
+            auto run = [&](auto r_tag, auto all_tag) {
+                constexpr int R = decltype(r_tag)::value;
+                constexpr bool ALL = decltype(all_tag)::value;     // a full group in the middle: every slice requests
+                auto one = [&](auto i_tag) {
+                    constexpr int I = decltype(i_tag)::value;
+                    if constexpr (I < R)
+                        slice(std::integral_constant<int, I % NS>{}, std::integral_constant<bool, ALL || (I < R - 1)>{},
+                              std::integral_constant<bool, ALL || (I + NS - 1 < R)>{});
+                };
+                one(std::integral_constant<int, 0>{});
+                one(std::integral_constant<int, 1>{});
+                one(std::integral_constant<int, 2>{});
+                one(std::integral_constant<int, 3>{});
+                one(std::integral_constant<int, 4>{});
+                one(std::integral_constant<int, 5>{});
+            };
+            static_assert(2 * NS - 2 <= 6, "the tail is written out for at most six slices");
             int kt = 0;
-            for (; kt + NS - 1 < nk; ++kt) slice(kt, std::true_type{}, std::true_type{});
-            for (; kt + 1 < nk; ++kt) slice(kt, std::true_type{}, std::false_type{});
-            slice(kt, std::false_type{}, std::false_type{});
+            if constexpr (BP * BC > 128 * 128) {
+                for (; kt + NS - 1 < nk; ++kt) slice(kt % NS, std::true_type{}, std::true_type{});
+                for (; kt + 1 < nk; ++kt) slice(kt % NS, std::true_type{}, std::false_type{});
+                slice(kt % NS, std::false_type{}, std::false_type{});
+            } else {
+                for (; kt + 2 * NS - 2 < nk; kt += NS) run(std::integral_constant<int, NS>{}, std::true_type{});
+                switch (nk - kt) {           // 1 .. 2*NS - 2 slices are left
+                    case 1: run(std::integral_constant<int, 1>{}, std::false_type{}); break;
+                    case 2: run(std::integral_constant<int, 2>{}, std::false_type{}); break;
+                    case 3: run(std::integral_constant<int, 3>{}, std::false_type{}); break;
+                    case 4: run(std::integral_constant<int, 4>{}, std::false_type{}); break;
+                    case 5: if constexpr (NS >= 4) run(std::integral_constant<int, 5>{}, std::false_type{}); break;
+                    default: if constexpr (NS >= 4) run(std::integral_constant<int, 6>{}, std::false_type{}); break;
+                }
+            }
         }
     } else {
         // Two stages: one K slice = wait for it, multiply it, and (MORE) request the next one in four
@@ -291,7 +359,7 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
             for (int ks = 0; ks < 4; ++ks) {
                 const int cur = ks & 1, nxt = cur ^ 1;
                 if (ks < 3) read_frags(nxt, st, ks + 1);
-                if constexpr (MORE) request_part(ks, 4);
+                if constexpr (MORE) request_part_rt(ks, 4);
                 multiply(cur);
             }
             __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);            // fragments of step 0
