@@ -109,6 +109,32 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
     const buffer_rsrc_t src_rs = make_buffer_rsrc(reinterpret_cast<const char*>(p.src) - margin, p.src_bytes + margin);
     const buffer_rsrc_t w_rs = make_buffer_rsrc(wmat, (unsigned)(K * p.Nc * 2));
     const int j8 = lane >> 3, pc = lane & 7;
+    // When the pixel rows need decoding (two divisions and the tap-validity mask per row), the weight copies of the
+    // first NS-1 slices go out before it: their addresses are ready, and the decoding runs under their latency.  A
+    // 1x1 / stride 1 source needs no decoding; there the copies go out slice by slice, pixels first (the pixel
+    // operand is the one that comes from HBM).
+    const bool weights_first = !(rc.linear & 1);
+    unsigned wrowb[LC];
+#pragma unroll
+    for (int i = 0; i < LC; ++i) {
+        const int lrow = 32 * i + 8 * wave + j8;
+        const int c = ch0 + lrow;
+        const int cl = pc ^ fast_swizzle(lrow);
+        wrowb[i] = c < p.Nc ? (unsigned)(c * (int)K + cl * 8) * 2u : kOutOfRange;
+    }
+    auto weight_copies = [&](int stage, unsigned soff, int first, int last) {
+#pragma unroll
+        for (int iw = 0; iw < LC; ++iw)
+            if (iw >= first && iw < last) dma16_buf_to_lds(w_rs, wrowb[iw], soff, lds + stage * STAGE + BP * 8 + (32 * iw + 8 * wave) * 8);
+    };
+    if (weights_first) {
+#pragma unroll
+        for (int s = 0; s < NS - 1; ++s)
+            if (s < nk) weight_copies(s, (unsigned)(s * 128), 0, LC);
+    }
+    auto low_bits = [](int n) -> unsigned { return n >= 32 ? 0xffffffffu : (1u << n) - 1u; };   // n in 0 .. 32
+    unsigned tap_rows = 0u;                // bit th * Tw set for every row of taps (at most 32 taps in all)
+    for (int th = 0; th < rc.Th; ++th) tap_rows |= 1u << (th * rc.Tw);
     unsigned rowb[LP];                     // byte offset of (row, tap 0, logical chunk), modulo 2^32
     unsigned badtap[LP];                   // bit t set: tap t of this row lies outside the image
 #pragma unroll
@@ -127,38 +153,28 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
                 const int rh = (int)fast_div((uint32_t)rem, rc.div_rw), rw = rem - rh * rc.Rw;
                 const int h0 = rh * rc.h_mul + rc.h_off, w0 = rw * rc.w_mul + rc.w_off;
                 rowb[i] = (unsigned)(((n * p.Hs + h0) * p.Ws + w0) * p.Cs + cl * 8) * 2u;
-                // taps th with 0 <= h0 + th * tap_step < Hs form one interval [lo, hi] (tap_step = +1 or -1)
-                auto bad_taps = [&](int v0, int extent, int taps) -> unsigned {
+                // Taps th with 0 <= h0 + th * tap_step < Hs form one interval [hl, hh] (tap_step = +1 or -1), likewise
+                // [wl, wh] along the width.  Tap (th, tw) is bit th * Tw + tw: the valid taps are the width interval
+                // repeated in every row of taps (one multiplication by the bit pattern 1, 1 << Tw, 1 << 2 Tw, ...),
+                // cut down to the rows hl .. hh.
+                auto interval = [&](int v0, int extent, int taps, int& l, int& h) {
                     const int lo = rc.tap_step > 0 ? -v0 : v0 - extent + 1;
                     const int hi = rc.tap_step > 0 ? extent - 1 - v0 : v0;
-                    const int l = lo > 0 ? lo : 0, h = hi < taps - 1 ? hi : taps - 1;
-                    const unsigned long long all = (1ull << taps) - 1ull;
-                    const unsigned long long good = h >= l ? ((1ull << (h + 1)) - 1ull) & ~((1ull << l) - 1ull) : 0ull;
-                    return (unsigned)(all & ~good);
+                    l = lo > 0 ? lo : 0;
+                    h = hi < taps - 1 ? hi : taps - 1;
                 };
-                const unsigned hbad = bad_taps(h0, p.Hs, rc.Th), wbad = bad_taps(w0, p.Ws, rc.Tw);
-                const unsigned wall = (unsigned)((1ull << rc.Tw) - 1ull);
-                unsigned bad = 0u;
-                if (rc.Th <= 8) {
-#pragma unroll
-                    for (int th = 0; th < 8; ++th)
-                        if (th < rc.Th) bad |= (((hbad >> th) & 1u) ? wall : wbad) << (th * rc.Tw);
-                } else {
-                    for (int th = 0; th < rc.Th; ++th) bad |= (((hbad >> th) & 1u) ? wall : wbad) << (th * rc.Tw);
+                int hl, hh, wl, wh;
+                interval(h0, p.Hs, rc.Th, hl, hh);
+                interval(w0, p.Ws, rc.Tw, wl, wh);
+                unsigned good = 0u;
+                if (hh >= hl && wh >= wl) {
+                    const unsigned wgood = low_bits(wh + 1) & ~low_bits(wl);
+                    good = (wgood * tap_rows) & low_bits((hh + 1) * rc.Tw) & ~low_bits(hl * rc.Tw);
                 }
-                badtap[i] = bad;
+                badtap[i] = ~good;
             }
         }
     }
-    unsigned wrowb[LC];
-#pragma unroll
-    for (int i = 0; i < LC; ++i) {
-        const int lrow = 32 * i + 8 * wave + j8;
-        const int c = ch0 + lrow;
-        const int cl = pc ^ fast_swizzle(lrow);
-        wrowb[i] = c < p.Nc ? (unsigned)(c * (int)K + cl * 8) * 2u : kOutOfRange;
-    }
-
     // Requests are issued slice by slice in ring order; a slice is requested in parts so that the copies can be issued
     // between the MFMAs of the slice being multiplied.  Everything a request needs is ready before it starts: the
     // scalar offsets of the next slice (pixel and weight operand) and, after a change of tap, the vector offsets are
@@ -171,34 +187,33 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
     unsigned voff[LP];                         // vector offset of this thread's pixel copies for the current tap:
 #pragma unroll                                 // all-ones where the tap lies outside the image
     for (int i = 0; i < LP; ++i) voff[i] = (rowb[i] + margin + (unsigned)delta_min) | (unsigned)__builtin_amdgcn_sbfe((int)badtap[i], 0, 1);
+    auto next_pixel_slice = [&]() {
+        if (__builtin_expect(++q_cs == cpt, 0)) {      // next tap (never taken again by a 1x1 layer)
+            q_cs = 0;
+            ++q_tap;
+            if (++q_tw == rc.Tw) {
+                q_tw = 0;
+                ++q_th;
+            }
+            s_pix = (unsigned)((((q_th * p.Ws + q_tw) * rc.tap_step) * p.Cs) * 2 - delta_min);
+#pragma unroll
+            for (int i = 0; i < LP; ++i)
+                voff[i] = (rowb[i] + margin + (unsigned)delta_min) | (unsigned)__builtin_amdgcn_sbfe((int)badtap[i], q_tap & 31, 1);
+        } else {
+            s_pix += 128u;
+        }
+    };
     auto request_part = [&](int stage, int part, int nparts) {
         uintx4* st = lds + stage * STAGE;
 #pragma unroll
         for (int i = 0; i < LPS; ++i) {
             if (i < (part * LPS) / nparts || i >= ((part + 1) * LPS) / nparts) continue;
-            if (i < LP) {
-                dma16_buf_to_lds(src_rs, voff[i], s_pix, st + (32 * i + 8 * wave) * 8);
-            } else {
-                const int iw = i - LP;
-                dma16_buf_to_lds(w_rs, wrowb[iw], s_w, st + BP * 8 + (32 * iw + 8 * wave) * 8);
-            }
+            if (i < LP) dma16_buf_to_lds(src_rs, voff[i], s_pix, st + (32 * i + 8 * wave) * 8);
+            else weight_copies(stage, s_w, i - LP, i - LP + 1);
         }
         if (part == nparts - 1) {
             s_w += 128u;
-            if (__builtin_expect(++q_cs == cpt, 0)) {      // next tap (never taken again by a 1x1 layer)
-                q_cs = 0;
-                ++q_tap;
-                if (++q_tw == rc.Tw) {
-                    q_tw = 0;
-                    ++q_th;
-                }
-                s_pix = (unsigned)((((q_th * p.Ws + q_tw) * rc.tap_step) * p.Cs) * 2 - delta_min);
-#pragma unroll
-                for (int i = 0; i < LP; ++i)
-                    voff[i] = (rowb[i] + margin + (unsigned)delta_min) | (unsigned)__builtin_amdgcn_sbfe((int)badtap[i], q_tap & 31, 1);
-            } else {
-                s_pix += 128u;
-            }
+            next_pixel_slice();
         }
     };
     // for the loops that do not know the ring stage at compile time
@@ -216,11 +231,16 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+    // pixel copies of the first NS-1 slices (with weights_first their weight copies are on their way already)
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s)
         if (s < nk) {
 #pragma unroll
-            for (int part = 0; part < 4; ++part) request_part_rt(part, 4);
+            for (int i = 0; i < LP; ++i) dma16_buf_to_lds(src_rs, voff[i], s_pix, lds + s * STAGE + (32 * i + 8 * wave) * 8);
+            if (!weights_first) weight_copies(s, s_w, 0, LC);
+            next_pixel_slice();
+            s_w += 128u;
+            q_stage = q_stage + 1 == NS ? 0 : q_stage + 1;
         }
 
     // LDS chunk index (inside a stage) of this lane's operand fragment for each of the 4 steps
@@ -306,9 +326,12 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
             fast_pin_copies_between_mfmas<MORE ? LPS - (2 * LPS) / 3 : 0, TC * TP>();
         };
 
-        // slice 0 must have landed; slices 1 .. NS-2 may still be in flight if that many exist
-        if (nk >= NS - 1) wait_vm_and_lds<(NS - 2) * LPS>();
-        else wait_vm_and_lds<0>();
+        // Slice 0 must have landed.  Requested slice by slice, slices 1 .. NS-2 may still be in flight.  Requested
+        // weights first, only the pixel copies of slice NS-2 were issued behind those of slice NS-3: that wait lets
+        // slices 0 .. NS-3 land (the in-loop waits count whole slices, which holds from slice NS-2 on).
+        if (nk < NS - 1) wait_vm_and_lds<0>();
+        else if (weights_first) wait_vm_and_lds<LP>();
+        else wait_vm_and_lds<(NS - 2) * LPS>();
         wg_barrier();
         if (nk > 0) {                // a row class without taps (strided data gradient) has nothing to multiply
             read_frags(0, lds, 0);
