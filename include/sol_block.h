@@ -156,7 +156,10 @@ SOL_API size_t sol_block_workspace_bytes(const sol_block_desc* desc, int pass);
  *   SOL_PLAN_DGRAD  data-gradient GEMM:  tile, stages
  *   SOL_PLAN_WGRAD  weight gradient:     splits (workgroups along N*Ho*Wo), stages
  * tile: 0 = 128 pixels x 128 channels, 1 = 128 x 64, 2 = 64 x 64, 3 = 256 x 128 (stages 2 or 3
- * only), -1 = library's choice.  stages: 2, 3 or 4 slices in flight, 0 = library's choice.
+ * only), 4 = 128-pixel panel kept in LDS while the workgroup walks over several 128-channel tiles
+ * (1x1 / stride 1 layers with 64 .. 256 input channels and a multiple of 128 output channels, no
+ * gate on the addend; ignored elsewhere; stages not used), -1 = library's choice.  stages: 2, 3 or
+ * 4 slices in flight, 0 = library's choice.
  * splits: 0 = library's choice; the workspace size of the backward pass depends on it, so install
  * plans before asking sol_block_workspace_bytes.  Plans only apply where the pipelined bf16 kernels
  * run; elsewhere they are ignored.  They change speed, never which result is correct: forward and

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsol_block.so")
-SOURCES = ["api.hip", "igemm.hip", "igemm_fast.hip", "wgrad.hip", "wgrad_fast.hip", "smallc.hip", "direct_f32.hip", "glue.hip", "runtime.hip"]
+SOURCES = ["api.hip", "igemm.hip", "igemm_fast.hip", "igemm_panel.hip", "wgrad.hip", "wgrad_fast.hip", "smallc.hip", "direct_f32.hip", "glue.hip", "runtime.hip"]
 HEADERS = ["common.h", "launch.h", "classes.h", "pack_tile.h", "sol_lds_tr.h", os.path.join("..", "..", "include", "sol_block.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

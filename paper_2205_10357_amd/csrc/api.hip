@@ -56,12 +56,12 @@ inline void clear_stale_error() { (void)hipGetLastError(); }
 // backward call used to make some fifteen of them.
 enum Knob {
     K_IGEMM_TILE, K_IGEMM_FAST, K_FAST_TILE, K_FAST_SHORTK, K_FAST_MANY, K_FAST_STAGES, K_WGRAD_SPLITS, K_WGRAD_TARGET,
-    K_SMALLC, K_FILL_UNTOUCHED, K_WGRAD_FAST, K_PACK_FUSED, K_WGRAD_STAGES, K_WGRAD_TICKET, K_PREMASK, K_COUNT
+    K_SMALLC, K_FILL_UNTOUCHED, K_WGRAD_FAST, K_PACK_FUSED, K_WGRAD_STAGES, K_WGRAD_TICKET, K_PREMASK, K_PANEL, K_PANEL_TILES, K_COUNT
 };
 const char* const kKnobNames[K_COUNT] = {
     "SOL_IGEMM_TILE", "SOL_IGEMM_FAST", "SOL_FAST_TILE", "SOL_FAST_SHORTK", "SOL_FAST_MANY", "SOL_FAST_STAGES",
     "SOL_WGRAD_SPLITS", "SOL_WGRAD_TARGET", "SOL_SMALLC", "SOL_FILL_UNTOUCHED", "SOL_WGRAD_FAST", "SOL_PACK_FUSED",
-    "SOL_WGRAD_STAGES", "SOL_WGRAD_TICKET", "SOL_PREMASK"};
+    "SOL_WGRAD_STAGES", "SOL_WGRAD_TICKET", "SOL_PREMASK", "SOL_PANEL", "SOL_PANEL_TILES"};
 constexpr int kKnobUnset = INT32_MIN;
 std::atomic<int> g_knobs[K_COUNT];
 std::atomic<bool> g_knobs_loaded{false};
@@ -142,6 +142,9 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& 
                          knob(K_IGEMM_FAST, 1) != 0;
     int bp, bc, tile = 0, stages = 0;
     bool many_tiles = false;
+    // 1x1 / stride 1 with a short reduction and a wide output: a workgroup keeps its pixel panel in LDS and walks over
+    // several channel tiles (tile code 4)
+    const bool panel_ok = fast_ok && knob(K_PANEL, 1) != 0 && igemm_panel_eligible(p);
     if (fast_ok) {
         long long slices = 0;
         for (int c = 0; c < p.ncls; ++c) {
@@ -149,8 +152,9 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& 
             if (s > slices) slices = s;
         }
         tile = knob(K_FAST_TILE, -1);
-        if (tile < 0 || tile > 3) tile = tuned.tile;              // an installed plan; the environment wins (experiments)
-        if (tile < 0 || tile > 3) {
+        if (tile < 0 || tile > 4) tile = tuned.tile;              // an installed plan; the environment wins (experiments)
+        if (tile == 4 && !panel_ok) tile = -1;                    // a plan for the panel kernel on a launch it cannot run
+        if (tile < 0 || tile > 4) {
             // 128 x 128 unless that leaves most compute units idle or the GEMM is narrow
             long long t128 = 0;
             for (int c = 0; c < p.ncls; ++c) t128 += (rows[c] + 127) / 128;
@@ -169,6 +173,17 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& 
             for (int c = 0; c < p.ncls; ++c) t += (rows[c] + bp - 1) / bp;
             t *= (p.Nc + bc - 1) / bc;
             if (t < 160) tile = 2;
+            // the panel kernel where its launch is one wave of workgroups that fills most of the chip
+            if (panel_ok) {
+                const long long panels = (rows[0] + 127) / 128;
+                long long groups = 256 / (panels > 0 ? panels : 1);
+                if (groups > p.Nc / 128) groups = p.Nc / 128;
+                if (panels <= 256 && panels * groups >= 160) tile = 4;
+            }
+        }
+        if (tile == 4) {
+            trace_point(stream, SOL_TRACE_IGEMM);
+            return launch_igemm_panel(p, knob(K_PANEL_TILES, 0), stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
         }
         stages = knob(K_FAST_STAGES, 0);
         if (stages < 2 || stages > 4) stages = tuned.stages;
@@ -691,7 +706,7 @@ SOL_API int sol_block_set_plan(const sol_block_desc* desc, int which, const sol_
     if (int e = check_desc(desc, &g)) return e;
     if (plan) {
         const bool stages_ok = plan->stages == 0 || (plan->stages >= 2 && plan->stages <= 4);
-        if (!stages_ok || plan->tile < -1 || plan->tile > 3 || (plan->tile == 3 && plan->stages == 4) ||
+        if (!stages_ok || plan->tile < -1 || plan->tile > 4 || (plan->tile == 3 && plan->stages == 4) ||
             plan->splits < 0 || plan->splits > 65535)
             return SOL_ERR_UNSUPPORTED;
     }

@@ -164,6 +164,8 @@ struct IgemmParams {
     int ncls;
     int tiles_c;                // channel tiles per pixel tile
     int total_tiles;
+    int panel_groups;           // panel kernel only: workgroups per 128-pixel panel ...
+    int panel_tiles;            // ... and 128-channel tiles each of them walks over
     RowClass cls[kMaxClasses];
 };
 

@@ -126,7 +126,7 @@ def test_launch_plans_are_a_host_side_table():
         # 20 splits of 128-row granularity over 12544 rows, fp32 partial tiles of 2304 x 256
         more = B.sol_block_workspace_bytes(d, B.SOL_PASS_BWD)
         assert more > base and (more - base) % (2304 * 256 * 4) < 64 * 1024
-        for bad in ((4, 2, 0), (-2, 2, 0), (0, 1, 0), (0, 5, 0), (3, 4, 0), (0, 2, -1), (0, 2, 70000)):
+        for bad in ((5, 2, 0), (-2, 2, 0), (0, 1, 0), (0, 5, 0), (3, 4, 0), (0, 2, -1), (0, 2, 70000)):
             assert B.sol_block_set_plan(d, B.SOL_PLAN_FWD, bad, check=False) == -4, bad
         assert B.sol_block_set_plan(d, 3, (0, 2, 0), check=False) == -4
         assert B.sol_block_set_plan(B.BlockDesc(0, 14, 14, 256, 256, 3, 3, 1, 1), 0, (0, 2, 0), check=False) == -2

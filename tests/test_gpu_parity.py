@@ -134,6 +134,52 @@ def test_every_installable_plan_matches_checker(shape):
         B.sol_clear_plans()
 
 
+PANEL_SHAPES = {
+    # forward runs the panel kernel (64 .. 256 input channels, output channels a multiple of 128) ...
+    "k64_to_384_res": dict(N=2, H=9, W=11, C_in=64, C_out=384, K=1, stride=1, pad=0, res=True),
+    "k192_to_512_ragged": dict(N=3, H=7, W=9, C_in=192, C_out=512, K=1, stride=1, pad=0, relu=False),
+    "k256_to_1024_res": dict(N=1, H=14, W=14, C_in=256, C_out=1024, K=1, stride=1, pad=0, res=True),
+    # ... the data gradient does where the roles are swapped (it gathers dy: C_out channels, writes C_in) ...
+    "dgrad_k128_to_256": dict(N=2, H=10, W=13, C_in=256, C_out=128, K=1, stride=1, pad=0),
+    "dgrad_k256_to_512": dict(N=1, H=12, W=11, C_in=512, C_out=256, K=1, stride=1, pad=0, relu=False),
+    # ... and both do here
+    "both_256": dict(N=2, H=14, W=14, C_in=256, C_out=256, K=1, stride=1, pad=0, res=True),
+}
+
+
+@pytest.mark.parametrize("tiles", [0, 1, 2, 3, 8], ids=lambda t: f"tiles{t}")
+@pytest.mark.parametrize("shape", list(PANEL_SHAPES), ids=list(PANEL_SHAPES))
+def test_panel_kernel_matches_checker(shape, tiles, sol_env):
+    """The kernel that keeps a pixel panel in LDS and walks over several channel tiles (plan tile 4), forced for the
+    forward and the data-gradient GEMM, with every number of tiles per workgroup from one (no streaming across tiles)
+    to more than the layer has (all in one workgroup): forward with and without residual, data gradient with an
+    addend and an output mask.  Compared with the CPU checker."""
+    if tiles:
+        sol_env("SOL_PANEL_TILES", tiles)
+    case = pu.make_case(91, **PANEL_SHAPES[shape])
+    d = case["d"]
+    desc = B.BlockDesc(d.N, d.H, d.W, d.C_in, d.C_out, d.KH, d.KW, d.stride, d.pad, B.SOL_BF16, 0)
+    r = np.random.default_rng(92)
+    dxm = wl.snap_to_bf16(np.maximum(r.standard_normal(case["x"].shape), 0).astype(np.float32))
+    ad = wl.snap_to_bf16(r.standard_normal(case["x"].shape).astype(np.float32))
+    try:
+        B.sol_block_set_plan(desc, B.SOL_PLAN_FWD, (4, 0, 0))
+        B.sol_block_set_plan(desc, B.SOL_PLAN_DGRAD, (4, 0, 0))
+        print(f"[panel] {shape}: tiles per workgroup {tiles or 'auto'}", flush=True)
+        got = pu.gpu_block(case, addend=ad, dx_mask=dxm, premasked=True)
+        errs = pu.check_block(case, got, addend=ad, dx_mask=dxm, premasked=True)
+        show(f"panel {shape} tiles {tiles}", errs)
+        # the same launches by the one-tile-per-workgroup kernel: identical bit for bit (same order of accumulation)
+        B.sol_block_set_plan(desc, B.SOL_PLAN_FWD, (0, 4, 0))
+        B.sol_block_set_plan(desc, B.SOL_PLAN_DGRAD, (0, 4, 0))
+        ref = pu.gpu_block(case, addend=ad, dx_mask=dxm, premasked=True)
+        for key in ("y", "dx"):
+            a, b = (np.ascontiguousarray(v[key], dtype=np.float32).view(np.uint32) for v in (got, ref))
+            assert np.array_equal(a, b), f"{key}: {int((a != b).sum())} elements differ from the one-tile kernel"
+    finally:
+        B.sol_clear_plans()
+
+
 @pytest.mark.parametrize("shape", [
     dict(N=1, H=1, W=1, C_in=8, C_out=8, K=3, stride=1, pad=1),               # single pixel, only the centre tap
     dict(N=3, H=5, W=7, C_in=16, C_out=24, K=3, stride=1, pad=1, res=True),   # fewer rows than one tile
