@@ -251,7 +251,8 @@ SOL_API int sol_sequence_run(const sol_sequence* seq, int32_t first, int32_t cou
 enum {
     SOL_TRACE_OTHER = 0, SOL_TRACE_IGEMM, SOL_TRACE_IGEMM_GENERAL, SOL_TRACE_WGRAD, SOL_TRACE_WGRAD_GENERAL,
     SOL_TRACE_WGRAD_REDUCE, SOL_TRACE_PACK, SOL_TRACE_UNTOUCHED, SOL_TRACE_MASKED_COPY, SOL_TRACE_SMALLC_PREPARE,
-    SOL_TRACE_SMALLC_FWD, SOL_TRACE_SMALLC_WGRAD, SOL_TRACE_DIRECT, SOL_TRACE_L1_GRAD, SOL_TRACE_MAXPOOL
+    SOL_TRACE_SMALLC_FWD, SOL_TRACE_SMALLC_WGRAD, SOL_TRACE_DIRECT, SOL_TRACE_L1_GRAD, SOL_TRACE_MAXPOOL,
+    SOL_TRACE_IGEMM_PANEL
 };
 typedef struct {
     int32_t kind;   /* SOL_TRACE_* */

@@ -182,7 +182,7 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& 
             }
         }
         if (tile == 4) {
-            trace_point(stream, SOL_TRACE_IGEMM);
+            trace_point(stream, SOL_TRACE_IGEMM_PANEL);
             return launch_igemm_panel(p, knob(K_PANEL_TILES, 0), stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
         }
         stages = knob(K_FAST_STAGES, 0);

@@ -332,9 +332,15 @@ __global__ __launch_bounds__(256) void igemm_panel_kernel(const IgemmParams p) {
     };
     static_assert(NK >= 1 && NK <= 4, "one to four K slices");
     for (int ti = 0; ti < t_count; ++ti) {
-        if (jpos + NK - 1 + NSW - 1 < J) run_tile(std::true_type{});
-        else run_tile(std::false_type{});
-        epilogue(ti);
+        // (the epilogue is instantiated behind either form of the tile so that the compiler, which places the waits
+        // for the epilogue operands, can count the weight copies issued since they were requested)
+        if (jpos + NK - 1 + NSW - 1 < J) {
+            run_tile(std::true_type{});
+            epilogue(ti);
+        } else {
+            run_tile(std::false_type{});
+            epilogue(ti);
+        }
         if (ti + 1 < t_count) request_epilogue_operands(ti + 1);
     }
 }

@@ -441,7 +441,8 @@ def test_prepared_step_and_launch_trace():
     assert len(trace) == 3 * per_step
     kinds = [B.sol_trace_kind_name(k) for k, _, _, _ in trace[:per_step]]
     print("[trace]", [(B.sol_trace_kind_name(k), tag, round(us, 1), round(at, 1)) for k, tag, us, at in trace[per_step:2 * per_step]], flush=True)
-    assert kinds.count("implicit GEMM (pipelined)") == 6 and kinds.count("weight-gradient GEMM (pipelined)") == 3
+    gemms = kinds.count("implicit GEMM (pipelined)") + kinds.count("implicit GEMM (pixel panel in LDS)")
+    assert gemms == 6 and kinds.count("weight-gradient GEMM (pipelined)") == 3
     assert kinds.count("split reduction") == 3 and kinds.count("L1-loss gradient") == 1
     assert [tag for _, tag, _, _ in trace[:per_step]] == [0, 1, 2, -2, 2, 2, 2, 1, 1, 1, 0, 0, 0]
     assert all(0.5 < us < 5000 for _, _, us, _ in trace)
