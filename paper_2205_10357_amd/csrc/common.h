@@ -65,8 +65,10 @@ __device__ __forceinline__ void dma16_to_lds(const void* gsrc, void* lds_wave_ba
                                      (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
 }
 // Same copy through a buffer descriptor: address = base + voff + soff, where soff is wave-uniform
-// (an SGPR: no vector instruction is spent on it) and a lane whose voff is >= the descriptor's
-// size reads zeros instead of memory (the range check ignores soff).
+// (an SGPR: no vector instruction is spent on it) and a lane whose offset is >= the descriptor's
+// size reads zeros instead of memory.  On gfx950 the range check is on voff + soff without
+// wrap-around (measured both ways: an all-ones voff plus any soff reads zeros, and so does an in-range
+// voff whose sum with soff passes the end), so a descriptor must span everything soff can reach.
 typedef __amdgpu_buffer_rsrc_t buffer_rsrc_t;
 __device__ __forceinline__ buffer_rsrc_t make_buffer_rsrc(const void* base, unsigned bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);

@@ -194,6 +194,9 @@ def test_panel_kernel_matches_checker(shape, tiles, sol_env):
     dict(N=1, H=33, W=31, C_in=64, C_out=136, K=3, stride=1, pad=1),          # ragged in pixels and channels
     dict(N=2, H=6, W=6, C_in=8, C_out=8, K=5, stride=1, pad=2),               # 5x5
     dict(N=1, H=8, W=8, C_in=16, C_out=16, K=3, stride=1, pad=0),             # no padding
+    dict(N=2, H=9, W=11, C_in=64, C_out=72, K=5, stride=1, pad=2, res=True),  # 25 taps on the pipelined kernel (tap mask, 5 tap rows)
+    dict(N=2, H=10, W=9, C_in=64, C_out=64, K=5, stride=2, pad=2),            # same, strided: four pixel classes with 9 / 6 / 6 / 4 taps
+    dict(N=1, H=6, W=7, C_in=128, C_out=64, K=3, stride=1, pad=2),            # padding 2 under a 3x3: border pixels lose two tap rows and two tap columns
 ])
 def test_bf16_edge_shapes(shape):
     case = pu.make_case(7, **shape)
