@@ -6,6 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsol_block.so")
+PROBE = os.path.join(HERE, "loop_model.bin")
 SOURCES = ["api.hip", "igemm.hip", "igemm_fast.hip", "igemm_panel.hip", "wgrad.hip", "wgrad_fast.hip", "smallc.hip", "direct_f32.hip", "glue.hip", "runtime.hip"]
 HEADERS = ["common.h", "launch.h", "classes.h", "pack_tile.h", "sol_lds_tr.h", os.path.join("..", "..", "include", "sol_block.h")]
 
@@ -53,6 +54,15 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if force or procs or _stale(LIB, objs):
         cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
         subprocess.run(cmd, check=True)
+    # the stand-alone timing model of the slice loop (an executable of its own, not part of the library)
+    probe_src = os.path.join(CSRC, "loop_model.hip")
+    if force or _stale(PROBE, [probe_src]):
+        cmd = [HIPCC, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+               "-packed-fp32-ops", probe_src, "-o", PROBE]
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if r.returncode != 0:
+            print("\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l), file=sys.stderr)
+            raise RuntimeError("hipcc failed on loop_model.hip")
     return LIB
 
 
