@@ -204,6 +204,43 @@ def test_bf16_edge_shapes(shape):
     show(f"edge {shape}", pu.check_block(case, got))
 
 
+def _random_pipelined_shapes(count, seed):
+    """Seeded draw of layer shapes the pipelined kernels take (input channels a multiple of 64, output channels a
+    multiple of 8): filter 1 / 3 / 5, stride 1 / 2, padding from none to one more than 'same', ragged pixel counts."""
+    r = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        k = int(r.choice([1, 3, 3, 5]))
+        stride = int(r.choice([1, 1, 2]))
+        pad = int(r.integers(0, k // 2 + 2)) if k > 1 else 0
+        c_in = int(r.choice([64, 128, 192, 256]))
+        c_out = int(r.choice([8, 24, 64, 72, 128, 136, 256, 384]))
+        n, h, w = int(r.integers(1, 4)), int(r.integers(5, 19)), int(r.integers(5, 19))
+        if h + 2 * pad < k or w + 2 * pad < k:
+            continue
+        out.append(dict(N=n, H=h, W=w, C_in=c_in, C_out=c_out, K=k, stride=stride, pad=pad,
+                        relu=bool(r.integers(0, 2)), res=bool(r.integers(0, 2))))
+    return out
+
+
+RANDOM_SHAPES = _random_pipelined_shapes(24, 20250)
+
+
+@pytest.mark.parametrize("idx", range(len(RANDOM_SHAPES)), ids=lambda i: "k{K}s{stride}p{pad}_{C_in}to{C_out}_{N}x{H}x{W}".format(**RANDOM_SHAPES[i]))
+def test_random_layer_shapes_on_the_pipelined_kernels(idx):
+    """Forward, data gradient (with an addend and an output mask) and weight gradient of seeded random layer shapes,
+    gradient masked upstream so that every GEMM runs on the pipelined kernels; compared with the CPU checker."""
+    shape = RANDOM_SHAPES[idx]
+    case = pu.make_case(300 + idx, **shape)
+    r = np.random.default_rng(400 + idx)
+    dxm = wl.snap_to_bf16(np.maximum(r.standard_normal(case["x"].shape), 0).astype(np.float32))
+    ad = wl.snap_to_bf16(r.standard_normal(case["x"].shape).astype(np.float32))
+    print(f"[random shape {idx}] {shape}", flush=True)
+    got = pu.gpu_block(case, addend=ad, dx_mask=dxm, premasked=True)
+    errs = pu.check_block(case, got, addend=ad, dx_mask=dxm, premasked=True)
+    show(f"random shape {idx}", errs)
+
+
 @pytest.mark.parametrize("tile", [0, 1, 2, 3])
 def test_bf16_every_tile_shape(tile, sol_env):
     sol_env("SOL_IGEMM_TILE", tile)
