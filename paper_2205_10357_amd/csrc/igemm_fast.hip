@@ -93,15 +93,13 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
     }
 
     // ---- what this thread copies: rows 32*i + 8*wave + (lane>>3), physical chunk lane&7 -------
-    // Copies go through buffer descriptors: per row a loop-invariant byte offset, per slice one
-    // wave-uniform tap / channel offset; a lane whose tap falls outside the image (or whose row
-    // does not exist) gets an out-of-range offset and reads zeros.
-    // The per-slice part of a pixel copy's address (tap and channel-slice offset) is wave-uniform and travels in the
-    // instruction's scalar offset, which must not be negative; the vector offset must stay inside the descriptor for
-    // every valid (row, tap).  Both hold once the descriptor starts `margin` bytes before the tensor: margin = how far
-    // tap 0 of the first pixel lies before the tensor (padding) plus how far the last tap lies before tap 0 (data
-    // gradient: taps walk backwards).  Only addresses inside the tensor are ever dereferenced: an invalid tap gets an
-    // out-of-range vector offset.
+    // Copies go through buffer descriptors: per row a loop-invariant vector offset, per slice one wave-uniform scalar
+    // offset (tap and channel slice); a lane whose tap falls outside the image (or whose row does not exist) gets an
+    // out-of-range vector offset and reads zeros.  The scalar offset must not be negative and the sum of the two
+    // offsets must stay inside the descriptor for every valid (row, tap) -- the range check is on the sum.  Both hold
+    // once the descriptor starts `margin` bytes before the tensor: margin = how far tap 0 of the first pixel lies
+    // before the tensor (padding) plus how far the last tap lies before tap 0 (data gradient: taps walk backwards).
+    // Only addresses inside the tensor are ever dereferenced.
     const int tap0_first = ((rc.h_off * p.Ws + rc.w_off) * p.Cs) * 2;
     const int tap_last = ((((rc.Th - 1) * p.Ws + (rc.Tw - 1)) * rc.tap_step) * p.Cs) * 2;
     const int delta_min = tap_last < 0 ? tap_last : 0;
