@@ -174,6 +174,9 @@ def per_launch_table(trace, wl, seq, B, steps):
         elif kname == "L1-loss gradient":
             role = "l1"
         fl, by, what = costs.get((role, tag), (0, 0, ""))
+        if kname.endswith("+ split reduction"):        # the launch also carries the reduction of the weight gradient
+            by += costs.get(("reduce", tag), (0, 0, ""))[1]
+            role = "dgrad + reduce"
         t_mfma = fl / (MFMA_BF16_PEAK_TFLOPS * 1e12) * 1e6
         t_hbm = by / (HBM_PEAK_GBS * 1e9) * 1e6
         rows.append({
@@ -260,7 +263,7 @@ def main():
     trace = B.sol_trace_stop(points)
     torch.cuda.synchronize()
     table = per_launch_table(trace, wl, seq, B, trace_steps)
-    dom = [r for r in table if r["kernel"] == "implicit GEMM (pipelined)"]
+    dom = [r for r in table if r["kernel"].startswith("implicit GEMM (pipelined)")]
     if dom:
         dom_flops = sum(r["gflop"] for r in dom) * 1e9
         dom_us = sum(r["us"] for r in dom)

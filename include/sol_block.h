@@ -247,12 +247,14 @@ SOL_API int sol_sequence_run(const sol_sequence* seq, int32_t first, int32_t cou
  * for; launches beyond it run untraced.  The events are created by sol_trace_start (the only place in the
  * library that creates HIP objects) and kept for later traces.
  * One trace at a time, all calls traced must use one stream; not for use under graph capture.
+ * The two ..._REDUCE kinds are data-gradient launches of sol_block_bwd that also carry the reduction of the same
+ * call's split weight gradient (as extra workgroups), which then is no launch of its own.
  */
 enum {
     SOL_TRACE_OTHER = 0, SOL_TRACE_IGEMM, SOL_TRACE_IGEMM_GENERAL, SOL_TRACE_WGRAD, SOL_TRACE_WGRAD_GENERAL,
     SOL_TRACE_WGRAD_REDUCE, SOL_TRACE_PACK, SOL_TRACE_UNTOUCHED, SOL_TRACE_MASKED_COPY, SOL_TRACE_SMALLC_PREPARE,
     SOL_TRACE_SMALLC_FWD, SOL_TRACE_SMALLC_WGRAD, SOL_TRACE_DIRECT, SOL_TRACE_L1_GRAD, SOL_TRACE_MAXPOOL,
-    SOL_TRACE_IGEMM_PANEL
+    SOL_TRACE_IGEMM_PANEL, SOL_TRACE_IGEMM_REDUCE, SOL_TRACE_IGEMM_PANEL_REDUCE
 };
 typedef struct {
     int32_t kind;   /* SOL_TRACE_* */

@@ -8,7 +8,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsol_block.so")
 PROBE = os.path.join(HERE, "loop_model.bin")
 SOURCES = ["api.hip", "igemm.hip", "igemm_fast.hip", "igemm_panel.hip", "wgrad.hip", "wgrad_fast.hip", "smallc.hip", "direct_f32.hip", "glue.hip", "runtime.hip"]
-HEADERS = ["common.h", "launch.h", "classes.h", "pack_tile.h", "sol_lds_tr.h", os.path.join("..", "..", "include", "sol_block.h")]
+HEADERS = ["common.h", "launch.h", "classes.h", "pack_tile.h", "reduce_rows.h", "sol_lds_tr.h", os.path.join("..", "..", "include", "sol_block.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -12,6 +12,7 @@
 #include "classes.h"
 #include "launch.h"
 #include "pack_tile.h"
+#include "reduce_rows.h"
 
 namespace sol {
 namespace {
@@ -56,12 +57,13 @@ inline void clear_stale_error() { (void)hipGetLastError(); }
 // backward call used to make some fifteen of them.
 enum Knob {
     K_IGEMM_TILE, K_IGEMM_FAST, K_FAST_TILE, K_FAST_SHORTK, K_FAST_MANY, K_FAST_STAGES, K_WGRAD_SPLITS, K_WGRAD_TARGET,
-    K_SMALLC, K_FILL_UNTOUCHED, K_WGRAD_FAST, K_PACK_FUSED, K_WGRAD_STAGES, K_WGRAD_TICKET, K_PREMASK, K_PANEL, K_PANEL_TILES, K_COUNT
+    K_SMALLC, K_FILL_UNTOUCHED, K_WGRAD_FAST, K_PACK_FUSED, K_WGRAD_STAGES, K_WGRAD_TICKET, K_PREMASK, K_PANEL, K_PANEL_TILES,
+    K_REDUCE_RIDES, K_COUNT
 };
 const char* const kKnobNames[K_COUNT] = {
     "SOL_IGEMM_TILE", "SOL_IGEMM_FAST", "SOL_FAST_TILE", "SOL_FAST_SHORTK", "SOL_FAST_MANY", "SOL_FAST_STAGES",
     "SOL_WGRAD_SPLITS", "SOL_WGRAD_TARGET", "SOL_SMALLC", "SOL_FILL_UNTOUCHED", "SOL_WGRAD_FAST", "SOL_PACK_FUSED",
-    "SOL_WGRAD_STAGES", "SOL_WGRAD_TICKET", "SOL_PREMASK", "SOL_PANEL", "SOL_PANEL_TILES"};
+    "SOL_WGRAD_STAGES", "SOL_WGRAD_TICKET", "SOL_PREMASK", "SOL_PANEL", "SOL_PANEL_TILES", "SOL_REDUCE_RIDES"};
 constexpr int kKnobUnset = INT32_MIN;
 std::atomic<int> g_knobs[K_COUNT];
 std::atomic<bool> g_knobs_loaded{false};
@@ -124,7 +126,28 @@ int pick_igemm_tile(const long long* class_rows, int ncls, int Nc) {
 // pipelined kernel (source channels % 64 == 0, output channels % 8 == 0, no mask on the gathered
 // operand) or the general one.  SOL_IGEMM_FAST=0 forces the general kernel; SOL_FAST_TILE /
 // SOL_FAST_STAGES override the pipelined kernel's tile and ring depth (tuning experiments).
-int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& tuned, hipStream_t stream) {
+// A pipelined or panel launch of `gemm_wgs` workgroups (one per compute unit at a time) can carry the split
+// reduction of the same block's weight gradient along, as workgroups behind its own: as many as its last wave
+// leaves compute units idle, so that the reduction runs beside the tiles instead of after them.  Returns 0 when
+// fewer than 32 are idle (the reduction then stays a launch of its own).  SOL_REDUCE_RIDES: 0 never, n > 1 that many.
+int reduce_rider_blocks(int gemm_wgs, const ReduceParams* rider) {
+    const int forced = knob(K_REDUCE_RIDES, 1);
+    if (!rider || forced == 0 || gemm_wgs <= 0 || !reduce_can_ride(*rider)) return 0;
+    if (forced > 1) return forced < 1024 ? forced : 1024;
+    const int idle = (256 - gemm_wgs % 256) % 256;
+    return idle >= 32 ? idle : 0;
+}
+
+// `rider`: a split reduction the launch may carry along (see above); *rode tells whether it did.
+int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& tuned, hipStream_t stream,
+              const ReduceParams* rider = nullptr, bool* rode = nullptr) {
+    if (rode) *rode = false;
+    auto attach = [&]() {            // p.total_tiles is final
+        p.red_blocks = reduce_rider_blocks(p.total_tiles, rider);
+        if (p.red_blocks > 0) p.red = *rider;
+        if (rode) *rode = p.red_blocks > 0;
+        return p.red_blocks > 0;
+    };
     bool few_taps = true;                       // the pipelined kernel keeps one validity bit per tap
     for (int c = 0; c < p.ncls; ++c) few_taps = few_taps && p.cls[c].Th * p.cls[c].Tw <= 32;
     // the pipelined kernel starts its buffer descriptor a few image rows before the gathered tensor (the reach of the
@@ -182,8 +205,9 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& 
             }
         }
         if (tile == 4) {
-            trace_point(stream, SOL_TRACE_IGEMM_PANEL);
-            return launch_igemm_panel(p, knob(K_PANEL_TILES, 0), stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
+            plan_igemm_panel(p, knob(K_PANEL_TILES, 0));
+            trace_point(stream, attach() ? SOL_TRACE_IGEMM_PANEL_REDUCE : SOL_TRACE_IGEMM_PANEL);
+            return launch_igemm_panel(p, stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
         }
         stages = knob(K_FAST_STAGES, 0);
         if (stages < 2 || stages > 4) stages = tuned.stages;
@@ -210,7 +234,8 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& 
     }
     p.total_tiles = tiles_p * p.tiles_c;
     hipError_t e;
-    trace_point(stream, fast_ok ? SOL_TRACE_IGEMM : SOL_TRACE_IGEMM_GENERAL);
+    const bool rides = fast_ok && tile != 1 && tile != 2 && attach();      // (the small tiles carry no reduction)
+    trace_point(stream, rides ? SOL_TRACE_IGEMM_REDUCE : fast_ok ? SOL_TRACE_IGEMM : SOL_TRACE_IGEMM_GENERAL);
     if (fast_ok) e = launch_igemm_fast(p, tile, stages, stream);
     else e = launch_igemm(p, tile, (p.Cs % 8) == 0, mask, stream);
     return e == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
@@ -357,7 +382,8 @@ int fwd_bf16(const sol_block_desc* d, const Geometry& g, const void* x, const vo
 }
 
 int dgrad_bf16(const sol_block_desc* d, const Geometry& g, const void* dy, const void* ymask, const bf16_t* wpack,
-               void* dx, const void* addend, const void* addend_mask, const void* dx_mask, hipStream_t stream) {
+               void* dx, const void* addend, const void* addend_mask, const void* dx_mask, hipStream_t stream,
+               const ReduceParams* rider = nullptr, bool* rode = nullptr) {
     const int s = d->stride;
     IgemmParams p{};
     const bool relu = ymask != nullptr;          // mask dy by y > 0 while gathering it
@@ -423,7 +449,7 @@ int dgrad_bf16(const sol_block_desc* d, const Geometry& g, const void* dy, const
         launch_untouched_pixels(dx, addend, addend_mask, dx_mask, d->N, d->H, d->W, d->C_in, d->KH, d->KW, s, d->pad,
                                 stream) != hipSuccess)
         return SOL_ERR_LAUNCH;
-    return run_igemm(p, rows, relu, installed_plan(d, SOL_PLAN_DGRAD), stream);
+    return run_igemm(p, rows, relu, installed_plan(d, SOL_PLAN_DGRAD), stream, rider, rode);
 }
 
 }  // namespace
@@ -589,6 +615,24 @@ static int bwd_common(const sol_block_desc* desc, const void* dy, const void* x,
                   desc->KW, desc->stride, desc->pad};
     const bool pack_rides = dx && dW && wgrad_pipelined && pack_tiled_ok(pk) && knob(K_PACK_FUSED, 1) != 0;
 
+    // The reduction of the split weight gradient in turn may ride along with the data-gradient launch (run_igemm
+    // decides); it needs the partial sums of the weight-gradient launch, which therefore goes first.
+    ReduceParams rp{};
+    rp.partial = partial;
+    rp.dshift_partial = dshift_partial;
+    rp.W = W;
+    rp.scale = scale;
+    rp.dW = dW;
+    rp.dscale = dscale;
+    rp.dshift = dshift;
+    rp.C_out = desc->C_out;
+    rp.K = (int)g.K;
+    rp.splits = plan.splits;
+    rp.accumulate = (desc->flags & SOL_DW_ACCUMULATE) ? 1 : 0;
+    rp.w_is_bf16 = desc->dtype == SOL_BF16 ? 1 : 0;
+    const bool reduce_may_ride = pack_rides;
+    bool reduce_rode = false;
+
     // ---- data branch: shortcut gradient, weight re-pack, data-gradient GEMM ----
     auto data_branch = [&](hipStream_t st) -> int {
         if (dres && !dres_done) {
@@ -599,7 +643,8 @@ static int bwd_common(const sol_block_desc* desc, const void* dy, const void* x,
         if (desc->dtype == SOL_BF16) {
             if (!pack_rides) trace_point(st, SOL_TRACE_PACK);
             if (!pack_rides && launch_pack_dgrad_weights(pk, st) != hipSuccess) return SOL_ERR_LAUNCH;
-            return dgrad_bf16(desc, g, dy, ymask, pk.out, dx, dx_addend, dx_addend_mask, dx_mask, st);
+            return dgrad_bf16(desc, g, dy, ymask, pk.out, dx, dx_addend, dx_addend_mask, dx_mask, st,
+                              reduce_may_ride ? &rp : nullptr, &reduce_rode);
         }
         DirectParams p = direct_params();
         trace_point(st, SOL_TRACE_DIRECT);
@@ -654,19 +699,7 @@ static int bwd_common(const sol_block_desc* desc, const void* dy, const void* x,
             trace_point(st, SOL_TRACE_DIRECT);
             if (launch_direct_wgrad_f32(p, st) != hipSuccess) return SOL_ERR_LAUNCH;
         }
-        ReduceParams rp{};
-        rp.partial = partial;
-        rp.dshift_partial = dshift_partial;
-        rp.W = W;
-        rp.scale = scale;
-        rp.dW = dW;
-        rp.dscale = dscale;
-        rp.dshift = dshift;
-        rp.C_out = desc->C_out;
-        rp.K = (int)g.K;
-        rp.splits = plan.splits;
-        rp.accumulate = (desc->flags & SOL_DW_ACCUMULATE) ? 1 : 0;
-        rp.w_is_bf16 = desc->dtype == SOL_BF16 ? 1 : 0;
+        if (reduce_may_ride) return SOL_OK;
         trace_point(st, SOL_TRACE_WGRAD_REDUCE);
         return launch_wgrad_reduce(rp, st) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
     };
@@ -676,6 +709,10 @@ static int bwd_common(const sol_block_desc* desc, const void* dy, const void* x,
     if (pack_rides) {
         status = weight_branch(stream);
         if (status == SOL_OK) status = data_branch(stream);
+        if (status == SOL_OK && !reduce_rode) {
+            trace_point(stream, SOL_TRACE_WGRAD_REDUCE);
+            if (launch_wgrad_reduce(rp, stream) != hipSuccess) status = SOL_ERR_LAUNCH;
+        }
     } else {
         status = data_branch(stream);
         if (status == SOL_OK && dW) status = weight_branch(stream);

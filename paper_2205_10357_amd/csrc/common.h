@@ -148,6 +148,18 @@ struct RowClass {
 
 constexpr int kMaxClasses = 4;
 
+// reduction of the split weight gradient (wgrad.hip, reduce_rows.h)
+struct ReduceParams {
+    const float* partial;       // [splits][C_out][K]
+    const float* dshift_partial;// [splits][C_out]
+    const void* W;              // [C_out][K] (bf16 or f32)
+    const float* scale;
+    float* dW;
+    float* dscale;
+    float* dshift;
+    int C_out, K, splits, accumulate, w_is_bf16;
+};
+
 struct IgemmParams {
     const bf16_t* src;          // gathered activation: x (forward) or dy (data gradient)
     const bf16_t* src_mask;     // data gradient with ReLU: the block's y (mask y > 0); else null
@@ -169,6 +181,10 @@ struct IgemmParams {
     int panel_groups;           // panel kernel only: workgroups per 128-pixel panel ...
     int panel_tiles;            // ... and 128-channel tiles each of them walks over
     RowClass cls[kMaxClasses];
+    // pipelined and panel kernels only: red_blocks > 0 appends that many workgroups to the launch, which finish the
+    // split weight gradient of the same block (rows red_block, red_block + red_blocks, ...) instead of multiplying
+    ReduceParams red;
+    int red_blocks;
 };
 
 // LDS read with transpose (16-bit elements): within each group of 16 lanes, the 16 x 8-byte
@@ -208,15 +224,5 @@ struct WgradParams {
     int pack_blocks;
 };
 
-struct ReduceParams {
-    const float* partial;       // [splits][C_out][K]
-    const float* dshift_partial;// [splits][C_out]
-    const void* W;              // [C_out][K] (bf16 or f32)
-    const float* scale;
-    float* dW;
-    float* dscale;
-    float* dshift;
-    int C_out, K, splits, accumulate, w_is_bf16;
-};
 
 }  // namespace sol

@@ -25,6 +25,7 @@
 #include <type_traits>
 
 #include "launch.h"
+#include "reduce_rows.h"
 
 namespace sol {
 
@@ -63,6 +64,10 @@ __global__ __launch_bounds__(256) void igemm_panel_kernel(const IgemmParams p) {
     SOL_FETCH_NOW_8(p.src, p.wmat, p.out, p.scale, p.shift, p.addend, p.out_mask, p.src_bytes);
     SOL_FETCH_NOW_8(p.Cs, p.Nc, p.relu, p.tiles_c, p.total_tiles, p.panel_groups, p.panel_tiles, rc.rows);
 
+    if ((int)blockIdx.x >= p.total_tiles) {    // workgroups behind the panels: split reduction of the weight gradient
+        reduce_rows_riding(p.red, (int)blockIdx.x - p.total_tiles, p.red_blocks, reinterpret_cast<float*>(lds));
+        return;
+    }
     const int bid = xcd_remap(blockIdx.x, p.total_tiles);
     // (the quotient is computed in vector registers; without the broadcast everything derived from it, the weight
     // descriptor included, would count as lane-dependent)
@@ -351,7 +356,7 @@ static hipError_t launch_panel(const IgemmParams& p, hipStream_t stream) {
     auto kern = igemm_panel_kernel<NK, HAS_OMASK>;
     static std::atomic<size_t> granted{0};
     if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), smem, granted); e != hipSuccess) return e;
-    SOL_LAUNCH(kern, dim3(p.total_tiles), dim3(256), smem, stream, p);
+    SOL_LAUNCH(kern, dim3(p.total_tiles + p.red_blocks), dim3(256), smem, stream, p);
     return hipGetLastError();
 }
 
@@ -367,11 +372,12 @@ bool igemm_panel_eligible(const IgemmParams& p) {
 }
 
 // Chooses how many channel tiles a workgroup walks over (the launch has panels x groups workgroups, at most one
-// wave of 256 where the shape allows; tiles_per_workgroup > 0 overrides, for tests and tuning) and launches.
-// p.total_tiles, p.panel_groups, p.panel_tiles are set here.
-hipError_t launch_igemm_panel(IgemmParams& p, int tiles_per_workgroup, hipStream_t stream) {
+// wave of 256 where the shape allows; tiles_per_workgroup > 0 overrides, for tests and tuning).
+// p.total_tiles (returned), p.panel_groups, p.panel_tiles are set here.
+int plan_igemm_panel(IgemmParams& p, int tiles_per_workgroup) {
     const int panels = (p.cls[0].rows + 127) / 128, tiles_c = p.Nc / 128;
-    if (panels <= 0) return hipSuccess;
+    p.total_tiles = 0;
+    if (panels <= 0) return 0;
     int groups = 256 / panels;
     if (groups < 1) groups = 1;
     if (groups > tiles_c) groups = tiles_c;
@@ -384,6 +390,12 @@ hipError_t launch_igemm_panel(IgemmParams& p, int tiles_per_workgroup, hipStream
     p.panel_tiles = per;
     p.total_tiles = panels * groups;
     p.cls[0].tile_begin = 0;
+    return p.total_tiles;
+}
+
+// A launch planned by plan_igemm_panel (p.red_blocks workgroups more when it carries a split reduction along).
+hipError_t launch_igemm_panel(const IgemmParams& p, hipStream_t stream) {
+    if (p.total_tiles <= 0) return hipSuccess;
     const bool om = p.out_mask != nullptr;
     switch (p.Cs / 64) {
         case 1: return om ? launch_panel<1, true>(p, stream) : launch_panel<1, false>(p, stream);

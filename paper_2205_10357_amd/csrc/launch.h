@@ -93,7 +93,8 @@ void igemm_tile_shape(int tile, int* bp, int* bc);
 hipError_t launch_igemm_fast(const IgemmParams& p, int tile, int stages, hipStream_t stream);
 void igemm_fast_tile_shape(int tile, int* bp, int* bc);
 bool igemm_panel_eligible(const IgemmParams& p);
-hipError_t launch_igemm_panel(IgemmParams& p, int tiles_per_workgroup, hipStream_t stream);
+int plan_igemm_panel(IgemmParams& p, int tiles_per_workgroup);
+hipError_t launch_igemm_panel(const IgemmParams& p, hipStream_t stream);
 hipError_t launch_wgrad(const WgradParams& p, bool vec, bool mask, hipStream_t stream);
 hipError_t launch_wgrad_fast(const WgradParams& p, int stages, hipStream_t stream);
 hipError_t launch_wgrad_reduce(const ReduceParams& p, hipStream_t stream);

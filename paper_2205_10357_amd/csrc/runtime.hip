@@ -112,6 +112,8 @@ SOL_API const char* sol_trace_kind_name(int32_t kind) {
         case SOL_TRACE_IGEMM: return "implicit GEMM (pipelined)";
         case SOL_TRACE_IGEMM_GENERAL: return "implicit GEMM (general)";
         case SOL_TRACE_IGEMM_PANEL: return "implicit GEMM (pixel panel in LDS)";
+        case SOL_TRACE_IGEMM_REDUCE: return "implicit GEMM (pipelined) + split reduction";
+        case SOL_TRACE_IGEMM_PANEL_REDUCE: return "implicit GEMM (pixel panel in LDS) + split reduction";
         case SOL_TRACE_WGRAD: return "weight-gradient GEMM (pipelined)";
         case SOL_TRACE_WGRAD_GENERAL: return "weight-gradient GEMM (general)";
         case SOL_TRACE_WGRAD_REDUCE: return "split reduction";

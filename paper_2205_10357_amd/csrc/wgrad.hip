@@ -13,6 +13,7 @@
 //   dshift[co] = sum_m g[m][co]            (column sums taken from the g blocks in registers)
 //   dscale[co] = sum_k W[co][k] * G[co][k] (equals sum_m g * conv(x,W), no z needed)
 #include "launch.h"
+#include "reduce_rows.h"
 
 namespace sol {
 
@@ -246,62 +247,19 @@ __global__ __launch_bounds__(256) void wgrad_bf16_kernel(const WgradParams p) {
 
 // One workgroup per output channel: fixed-order sum over the splits, dW = scale * G,
 // dscale = <W[co,:], G[co,:]> via wavefront shuffles, dshift = sum of the split column sums.
-// VEC: K % 4 == 0, 16-byte loads; the split loop keeps up to 16 loads in flight per thread (the order of
-// the additions stays fixed).
+// VEC: the row reduction of reduce_rows.h with the whole workgroup on one row (K % 4 == 0, partial sums below 2 GB);
+// else element by element.
 template <bool VEC>
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const ReduceParams p) {
-    const int co = blockIdx.x, tid = threadIdx.x;
-    const float sc = p.scale[co];
-    const long long row = (long long)co * p.K;
-    const long long split_stride = (long long)p.C_out * p.K;
-    float dot = 0.f;
+    __shared__ float sums[kReduceLdsFloats];
     if constexpr (VEC) {
-        for (int k = tid * 4; k < p.K; k += 1024) {
-            const float* src = p.partial + row + k;
-            floatx4 g = {0.f, 0.f, 0.f, 0.f};
-            int s = 0;
-            for (; s + 16 <= p.splits; s += 16) {        // 16 independent loads in flight, fixed add order
-                floatx4 a[16];
-#pragma unroll
-                for (int u = 0; u < 16; ++u) a[u] = *reinterpret_cast<const floatx4*>(src + (s + u) * split_stride);
-#pragma unroll
-                for (int u = 0; u < 16; ++u) g += a[u];
-            }
-            if (s + 8 <= p.splits) {
-                floatx4 a[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) a[u] = *reinterpret_cast<const floatx4*>(src + (s + u) * split_stride);
-#pragma unroll
-                for (int u = 0; u < 8; ++u) g += a[u];
-                s += 8;
-            }
-            {
-                floatx4 a[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    a[u] = s + u < p.splits ? *reinterpret_cast<const floatx4*>(src + (s + u) * split_stride)
-                                            : floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int u = 0; u < 8; ++u) g += a[u];
-            }
-            float w[4];
-            if (p.w_is_bf16) {
-                const uintx2 wb = *reinterpret_cast<const uintx2*>(reinterpret_cast<const bf16_t*>(p.W) + row + k);
-                w[0] = __uint_as_float(wb[0] << 16);
-                w[1] = __uint_as_float(wb[0] & 0xffff0000u);
-                w[2] = __uint_as_float(wb[1] << 16);
-                w[3] = __uint_as_float(wb[1] & 0xffff0000u);
-            } else {
-                const floatx4 wf = *reinterpret_cast<const floatx4*>(reinterpret_cast<const float*>(p.W) + row + k);
-                w[0] = wf[0]; w[1] = wf[1]; w[2] = wf[2]; w[3] = wf[3];
-            }
-#pragma unroll
-            for (int e = 0; e < 4; ++e) dot = fmaf(w[e], g[e], dot);
-            floatx4 d = {sc * g[0], sc * g[1], sc * g[2], sc * g[3]};
-            if (p.accumulate) d += *reinterpret_cast<const floatx4*>(p.dW + row + k);
-            *reinterpret_cast<floatx4*>(p.dW + row + k) = d;
-        }
+        reduce_rows_vec<256, 1>(p, blockIdx.x, gridDim.x, sums);
     } else {
+        const int co = blockIdx.x, tid = threadIdx.x;
+        const float sc = p.scale[co];
+        const long long row = (long long)co * p.K;
+        const long long split_stride = (long long)p.C_out * p.K;
+        float dot = 0.f;
         for (int k = tid; k < p.K; k += 256) {
             float g = 0.f;
             for (int s = 0; s < p.splits; ++s) g += p.partial[s * split_stride + row + k];
@@ -311,25 +269,23 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const ReduceParams p)
             const float d = sc * g;
             p.dW[row + k] = p.accumulate ? p.dW[row + k] + d : d;
         }
-    }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
-    // column sums of the splits: every thread fetches its share at once (a single thread walking the
-    // splits would pay one memory latency per split), then a fixed-order sum
-    float mine = 0.f;
-    for (int s2 = tid; s2 < p.splits; s2 += 256) mine += p.dshift_partial[(long long)s2 * p.C_out + co];
-    __shared__ float wsum[4];
-    __shared__ float ssum[256];
-    if ((tid & 63) == 0) wsum[tid >> 6] = dot;
-    ssum[tid] = mine;
-    __syncthreads();
-    if (tid == 0) {
-        const float ds = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
-        float db = 0.f;
-        const int n = p.splits < 256 ? p.splits : 256;
-        for (int s2 = 0; s2 < n; ++s2) db += ssum[s2];
-        p.dscale[co] = p.accumulate ? p.dscale[co] + ds : ds;
-        p.dshift[co] = p.accumulate ? p.dshift[co] + db : db;
+        for (int off = 32; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
+        float mine = 0.f;
+        for (int s2 = tid; s2 < p.splits; s2 += 256) mine += p.dshift_partial[(long long)s2 * p.C_out + co];
+        float* ssum = sums;
+        float* wsum = sums + 256;
+        if ((tid & 63) == 0) wsum[tid >> 6] = dot;
+        ssum[tid] = mine;
+        __syncthreads();
+        if (tid == 0) {
+            const float ds = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+            float db = 0.f;
+            const int n = p.splits < 256 ? p.splits : 256;
+            for (int s2 = 0; s2 < n; ++s2) db += ssum[s2];
+            p.dscale[co] = p.accumulate ? p.dscale[co] + ds : ds;
+            p.dshift[co] = p.accumulate ? p.dshift[co] + db : db;
+        }
     }
 }
 
@@ -348,7 +304,7 @@ hipError_t launch_wgrad(const WgradParams& p, bool vec, bool mask, hipStream_t s
 }
 
 hipError_t launch_wgrad_reduce(const ReduceParams& p, hipStream_t stream) {
-    if ((p.K & 3) == 0) SOL_LAUNCH(wgrad_reduce_kernel<true>, dim3(p.C_out), dim3(256), 0, stream, p);
+    if (reduce_rows_ok(p)) SOL_LAUNCH(wgrad_reduce_kernel<true>, dim3(p.C_out), dim3(256), 0, stream, p);
     else SOL_LAUNCH(wgrad_reduce_kernel<false>, dim3(p.C_out), dim3(256), 0, stream, p);
     return hipGetLastError();
 }

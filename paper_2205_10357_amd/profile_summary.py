@@ -30,7 +30,7 @@ import statistics
 from collections import defaultdict
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-KERNEL_SOURCES = ("igemm_fast.hip", "api.hip", "common.h")
+KERNEL_SOURCES = ("igemm_fast.hip", "reduce_rows.h", "api.hip", "common.h")
 COPY_KERNEL = "__amd_rocclr_copyBuffer"
 COPY_BYTES = 256 << 20
 ANCHOR = "l1_grad_kernel"

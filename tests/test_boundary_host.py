@@ -162,8 +162,8 @@ def test_prepared_sequence_records_on_the_host_and_reports_the_failing_call():
 
 
 def test_trace_kind_names_and_stop_without_start():
-    names = {B.sol_trace_kind_name(k) for k in range(0, 16)}
-    assert len(names) == 16 and "unknown" not in names
+    names = {B.sol_trace_kind_name(k) for k in range(0, 18)}
+    assert len(names) == 18 and "unknown" not in names
     assert B.sol_trace_kind_name(99) == "unknown"
     import ctypes as C
     n = C.c_int32(7)

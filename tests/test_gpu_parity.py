@@ -274,6 +274,59 @@ def test_bf16_wgrad_split_counts(splits, sol_env):
     show(f"splits{splits}", pu.check_block(case, got))
 
 
+RIDING_SHAPES = {
+    # name: (block, plan tile of the data-gradient GEMM); K = KH * KW * C_in decides the team width and the chunks
+    "k64_one_wave_per_row": (dict(N=2, H=9, W=11, C_in=64, C_out=192, K=1, stride=1, pad=0, relu=False), 0),
+    "k256_one_wave_per_row": (dict(N=1, H=12, W=11, C_in=256, C_out=128, K=1, stride=1, pad=0, relu=False), 0),
+    "k512_two_waves_per_row": (dict(N=2, H=7, W=9, C_in=512, C_out=64, K=1, stride=1, pad=0, relu=False), 3),
+    "k576_whole_workgroup": (dict(N=2, H=10, W=9, C_in=64, C_out=128, K=3, stride=1, pad=1, relu=False), 0),
+    "k1152_two_chunks": (dict(N=1, H=11, W=10, C_in=128, C_out=64, K=3, stride=1, pad=1, relu=False), 0),
+    "k2304_three_chunks": (dict(N=1, H=9, W=9, C_in=256, C_out=192, K=3, stride=1, pad=1, relu=False), 3),
+    "k4608_two_passes_stride2": (dict(N=1, H=9, W=10, C_in=512, C_out=64, K=3, stride=2, pad=1, relu=False), 0),
+    "panel_k128_to_256": (dict(N=2, H=10, W=13, C_in=256, C_out=128, K=1, stride=1, pad=0, relu=False), 4),
+}
+
+
+@pytest.mark.parametrize("riders", [1, 3, 40], ids=lambda r: "riders_auto" if r == 1 else f"riders{r}")
+@pytest.mark.parametrize("shape", list(RIDING_SHAPES), ids=list(RIDING_SHAPES))
+def test_split_reduction_riding_with_the_data_gradient(shape, riders, sol_env):
+    """A backward call that computes both branches with the pipelined kernels appends the reduction of the split weight
+    gradient to the data-gradient launch (workgroups behind the tiles): every team width and chunk count of the row
+    reduction, on the 128 x 128, 256 x 128 and panel kernels, with the library's own number of riding workgroups, with
+    3 (every workgroup walks over many rows) and with 40, and with the accumulate flag.  The launch trace shows that
+    the reduction rode; results are compared with the CPU checker and, bit for bit, with the reduction as a launch
+    of its own."""
+    spec, tile = RIDING_SHAPES[shape]
+    case = pu.make_case(131, **spec)
+    d = case["d"]
+    r = np.random.default_rng(132)
+    init = r.standard_normal(case["w"].shape).astype(np.float32)
+    try:
+        for flags in (0, B.SOL_DW_ACCUMULATE):
+            desc = B.BlockDesc(d.N, d.H, d.W, d.C_in, d.C_out, d.KH, d.KW, d.stride, d.pad, B.SOL_BF16, flags)
+            B.sol_block_set_plan(desc, B.SOL_PLAN_DGRAD, (tile, 2 if tile == 3 else 0, 0))
+        out = {}
+        for mode in (riders, 0):
+            sol_env("SOL_REDUCE_RIDES", mode)
+            print(f"[riding] {shape}: SOL_REDUCE_RIDES={mode}", flush=True)
+            B.sol_trace_start(64)
+            plain = pu.gpu_block(case)
+            acc = pu.gpu_block(case, accumulate=True, dw_init=init)
+            kinds = [B.sol_trace_kind_name(k) for k, _, _, _ in B.sol_trace_stop(64)]
+            rode = sum("+ split reduction" in k for k in kinds)
+            alone = kinds.count("split reduction")
+            assert (rode, alone) == ((2, 0) if mode else (0, 2)), kinds
+            out[mode] = (plain, acc)
+        show(f"riding {shape} riders {riders}", pu.check_block(case, out[riders][0]))
+        for which in (0, 1):
+            for key in ("dx", "dW", "dscale", "dshift"):
+                a, b = out[riders][which][key], out[0][which][key]
+                assert np.array_equal(a, b), f"{key} (accumulate={which}): {int((a != b).sum())} elements differ"
+        np.testing.assert_allclose(out[riders][1]["dW"], out[riders][0]["dW"] + init, rtol=1e-6, atol=1e-7)
+    finally:
+        B.sol_clear_plans()
+
+
 def test_bf16_addend_mask_and_accumulate():
     case = pu.make_case(11, 2, 10, 9, 16, 24, 3, 1, 1, res=True)
     r = np.random.default_rng(12)
