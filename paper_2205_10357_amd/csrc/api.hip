@@ -129,11 +129,18 @@ int pick_igemm_tile(const long long* class_rows, int ncls, int Nc) {
 // A pipelined or panel launch of `gemm_wgs` workgroups (one per compute unit at a time) can carry the split
 // reduction of the same block's weight gradient along, as workgroups behind its own: as many as its last wave
 // leaves compute units idle, so that the reduction runs beside the tiles instead of after them.  Returns 0 when
-// fewer than 32 are idle (the reduction then stays a launch of its own).  SOL_REDUCE_RIDES: 0 never, n > 1 that many.
-int reduce_rider_blocks(int gemm_wgs, const ReduceParams* rider) {
+// fewer than 32 are idle (the reduction then stays a launch of its own).  The two smaller tiles run several workgroups
+// per compute unit in many waves: there the riders fill the launch's tail, one per compute unit at most and no more
+// than there are passes over the rows.  SOL_REDUCE_RIDES: 0 never, n > 1 that many.
+int reduce_rider_blocks(int gemm_wgs, bool small_tile, const ReduceParams* rider) {
     const int forced = knob(K_REDUCE_RIDES, 1);
     if (!rider || forced == 0 || gemm_wgs <= 0 || !reduce_can_ride(*rider)) return 0;
     if (forced > 1) return forced < 1024 ? forced : 1024;
+    if (small_tile) {
+        const int rows_per_pass = rider->K <= 256 ? 4 : (rider->K <= 512 ? 2 : 1);
+        const int passes = (rider->C_out + rows_per_pass - 1) / rows_per_pass;
+        return passes < 256 ? passes : 256;
+    }
     const int idle = (256 - gemm_wgs % 256) % 256;
     return idle >= 32 ? idle : 0;
 }
@@ -142,8 +149,8 @@ int reduce_rider_blocks(int gemm_wgs, const ReduceParams* rider) {
 int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& tuned, hipStream_t stream,
               const ReduceParams* rider = nullptr, bool* rode = nullptr) {
     if (rode) *rode = false;
-    auto attach = [&]() {            // p.total_tiles is final
-        p.red_blocks = reduce_rider_blocks(p.total_tiles, rider);
+    auto attach = [&](bool small_tile) {            // p.total_tiles is final
+        p.red_blocks = reduce_rider_blocks(p.total_tiles, small_tile, rider);
         if (p.red_blocks > 0) p.red = *rider;
         if (rode) *rode = p.red_blocks > 0;
         return p.red_blocks > 0;
@@ -206,7 +213,7 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& 
         }
         if (tile == 4) {
             plan_igemm_panel(p, knob(K_PANEL_TILES, 0));
-            trace_point(stream, attach() ? SOL_TRACE_IGEMM_PANEL_REDUCE : SOL_TRACE_IGEMM_PANEL);
+            trace_point(stream, attach(false) ? SOL_TRACE_IGEMM_PANEL_REDUCE : SOL_TRACE_IGEMM_PANEL);
             return launch_igemm_panel(p, stream) == hipSuccess ? SOL_OK : SOL_ERR_LAUNCH;
         }
         stages = knob(K_FAST_STAGES, 0);
@@ -234,7 +241,7 @@ int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& 
     }
     p.total_tiles = tiles_p * p.tiles_c;
     hipError_t e;
-    const bool rides = fast_ok && tile != 1 && tile != 2 && attach();      // (the small tiles carry no reduction)
+    const bool rides = fast_ok && attach(tile == 1 || tile == 2);
     trace_point(stream, rides ? SOL_TRACE_IGEMM_REDUCE : fast_ok ? SOL_TRACE_IGEMM : SOL_TRACE_IGEMM_GENERAL);
     if (fast_ok) e = launch_igemm_fast(p, tile, stages, stream);
     else e = launch_igemm(p, tile, (p.Cs % 8) == 0, mask, stream);

@@ -59,11 +59,11 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
     SOL_FETCH_NOW_8(rc.w_off, rc.Th, rc.Tw, rc.tap_step, rc.oh_mul, rc.oh_off, rc.ow_mul, rc.ow_off);
     SOL_FETCH_NOW_8(rc.tile_begin, rc.linear, rc.b_off, rc.div_img.magic, rc.div_img.shift, rc.div_rw.magic,
                     rc.div_rw.shift, p.total_tiles);
-    if constexpr (BP * BC >= 128 * 128) {      // (the smaller tiles live on several workgroups per compute unit: no registers for this)
-        if ((int)blockIdx.x >= p.total_tiles) {    // workgroups behind the tiles: split reduction of the weight gradient
-            reduce_rows_riding(p.red, (int)blockIdx.x - p.total_tiles, p.red_blocks, reinterpret_cast<float*>(lds));
-            return;
-        }
+    if ((int)blockIdx.x >= p.total_tiles) {    // workgroups behind the tiles: split reduction of the weight gradient
+        // (the smaller tiles live on several workgroups per compute unit: the form that needs few registers)
+        reduce_rows_riding<(BP * BC < 128 * 128)>(p.red, (int)blockIdx.x - p.total_tiles, p.red_blocks,
+                                                  reinterpret_cast<float*>(lds));
+        return;
     }
     const int bid = xcd_remap(blockIdx.x, p.total_tiles);     // total_tiles workgroups multiply
     const int tc = bid % p.tiles_c;
@@ -531,7 +531,6 @@ static hipError_t launch_fast_tile(const IgemmParams& p, hipStream_t stream) {
 // tile: 0 = 128 x 128, 1 = 128 pixels x 64 channels, 2 = 64 x 64, 3 = 256 x 128; stages: 2, 3 or 4
 hipError_t launch_igemm_fast(const IgemmParams& p, int tile, int stages, hipStream_t stream) {
     if (p.total_tiles <= 0) return hipSuccess;
-    if (p.red_blocks > 0 && (tile == 1 || tile == 2)) return hipErrorInvalidValue;     // the small tiles carry no reduction
     switch (tile * 8 + stages) {
         case 0 * 8 + 2: return launch_fast_tile<128, 128, 2, 2, 2>(p, stream);
         case 0 * 8 + 3: return launch_fast_tile<128, 128, 2, 2, 3>(p, stream);

@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void igemm_panel_kernel(const IgemmParams p) {
     SOL_FETCH_NOW_8(p.Cs, p.Nc, p.relu, p.tiles_c, p.total_tiles, p.panel_groups, p.panel_tiles, rc.rows);
 
     if ((int)blockIdx.x >= p.total_tiles) {    // workgroups behind the panels: split reduction of the weight gradient
-        reduce_rows_riding(p.red, (int)blockIdx.x - p.total_tiles, p.red_blocks, reinterpret_cast<float*>(lds));
+        reduce_rows_riding<false>(p.red, (int)blockIdx.x - p.total_tiles, p.red_blocks, reinterpret_cast<float*>(lds));
         return;
     }
     const int bid = xcd_remap(blockIdx.x, p.total_tiles);

@@ -7,7 +7,7 @@ namespace sol {
 
 // floats of LDS the row reduction needs (256 split sums + 4 wave sums)
 constexpr int kReduceLdsFloats = 260;
-// splits a thread has in flight per chunk; reads of up to this many splits beyond the last are issued (and return 0)
+// most splits a thread has in flight per chunk; reads of up to this many splits beyond the last are issued (and return 0)
 constexpr int kReduceBatch = 16;
 
 // The partial sums are read through a buffer descriptor (out-of-range reads return 0, which is how missing splits and
@@ -28,10 +28,11 @@ inline bool reduce_rows_ok(const ReduceParams& p) {
 // kReduceLdsFloats floats of LDS.  All 256 threads must call (barriers inside).
 // (A compute unit whose loads miss the L2 moves about 25 GB/s whatever it has in flight beyond this: two rows per
 // team at once took as long per byte.)
-template <int TS, int CH>
+template <int TS, int CH, int BATCH = kReduceBatch>
 __device__ __forceinline__ void reduce_rows_vec(const ReduceParams& p, int block, int nblocks, float* scratch) {
     static_assert(TS == 64 || TS == 128 || TS == 256, "one, two or four waves per row");
-    constexpr int TEAMS = 256 / TS, BATCH = kReduceBatch;
+    static_assert(BATCH >= 1 && BATCH <= kReduceBatch, "reduce_rows_ok allows for kReduceBatch splits beyond the last");
+    constexpr int TEAMS = 256 / TS;
     const int tid = threadIdx.x, team = tid / TS, t = tid % TS;
     const unsigned split_bytes = (unsigned)p.C_out * (unsigned)p.K * 4u;
     const buffer_rsrc_t part_rs = make_buffer_rsrc(p.partial, (unsigned)p.splits * split_bytes);
@@ -115,12 +116,15 @@ __device__ __forceinline__ void reduce_rows_vec(const ReduceParams& p, int block
 
 // Workgroup `block` of `nblocks` that ride along with another kernel's launch: the narrowest team that covers a row,
 // up to three chunks per thread at a time where rows are longer than the workgroup.
+// SLIM: for host kernels with a small register budget (one chunk, 8 splits in flight).
+template <bool SLIM>
 __device__ __forceinline__ void reduce_rows_riding(const ReduceParams& p, int block, int nblocks, float* scratch) {
-    if (p.K <= 256) reduce_rows_vec<64, 1>(p, block, nblocks, scratch);
-    else if (p.K <= 512) reduce_rows_vec<128, 1>(p, block, nblocks, scratch);
-    else if (p.K <= 1024) reduce_rows_vec<256, 1>(p, block, nblocks, scratch);
-    else if (p.K <= 2048) reduce_rows_vec<256, 2>(p, block, nblocks, scratch);
-    else reduce_rows_vec<256, 3>(p, block, nblocks, scratch);
+    constexpr int B = SLIM ? 8 : kReduceBatch;
+    if (p.K <= 256) reduce_rows_vec<64, 1, B>(p, block, nblocks, scratch);
+    else if (p.K <= 512) reduce_rows_vec<128, 1, B>(p, block, nblocks, scratch);
+    else if (SLIM || p.K <= 1024) reduce_rows_vec<256, 1, B>(p, block, nblocks, scratch);
+    else if (p.K <= 2048) reduce_rows_vec<256, 2, B>(p, block, nblocks, scratch);
+    else reduce_rows_vec<256, 3, B>(p, block, nblocks, scratch);
 }
 
 // what a launch must satisfy to carry the reduction along (the narrow teams hold one split sum per thread)

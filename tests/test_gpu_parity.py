@@ -284,6 +284,10 @@ RIDING_SHAPES = {
     "k2304_three_chunks": (dict(N=1, H=9, W=9, C_in=256, C_out=192, K=3, stride=1, pad=1, relu=False), 3),
     "k4608_two_passes_stride2": (dict(N=1, H=9, W=10, C_in=512, C_out=64, K=3, stride=2, pad=1, relu=False), 0),
     "panel_k128_to_256": (dict(N=2, H=10, W=13, C_in=256, C_out=128, K=1, stride=1, pad=0, relu=False), 4),
+    # the two smaller tiles carry the form of the reduction that needs few registers (one chunk, 8 splits in flight)
+    "k128_tile_128x64": (dict(N=2, H=9, W=11, C_in=128, C_out=192, K=1, stride=1, pad=0, relu=False), 1),
+    "k1152_tile_128x64": (dict(N=1, H=11, W=10, C_in=128, C_out=64, K=3, stride=1, pad=1, relu=False), 1),
+    "k576_tile_64x64": (dict(N=2, H=10, W=9, C_in=64, C_out=128, K=3, stride=1, pad=1, relu=False), 2),
 }
 
 
@@ -292,7 +296,7 @@ RIDING_SHAPES = {
 def test_split_reduction_riding_with_the_data_gradient(shape, riders, sol_env):
     """A backward call that computes both branches with the pipelined kernels appends the reduction of the split weight
     gradient to the data-gradient launch (workgroups behind the tiles): every team width and chunk count of the row
-    reduction, on the 128 x 128, 256 x 128 and panel kernels, with the library's own number of riding workgroups, with
+    reduction, on every tile of the pipelined kernel and on the panel kernel, with the library's own number of riding workgroups, with
     3 (every workgroup walks over many rows) and with 40, and with the accumulate flag.  The launch trace shows that
     the reduction rode; results are compared with the CPU checker and, bit for bit, with the reduction as a launch
     of its own."""
