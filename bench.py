@@ -277,6 +277,14 @@ def main():
                     "sum_us": round(dom_us, 2),
                     "largest_launch": {"launch": big["launch"], "us": big["us"], "algorithmic_bytes": big["bytes"],
                                        "frac": round(big["pct_mfma_peak"] / 100, 4)}}
+        # the same figure over the launches that only multiply (the others also carry a split reduction, whose time
+        # is in `achieved` above but whose work is bytes, not flops)
+        plain = [r for r in dom if r["kernel"] == "implicit GEMM (pipelined)"]
+        if plain and len(plain) < len(dom):
+            pf, pu = sum(r["gflop"] for r in plain) * 1e9, sum(r["us"] for r in plain)
+            roofline["launches_without_riding_reduction"] = {
+                "launches_per_step": len(plain), "sum_us": round(pu, 2), "achieved": round(pf / (pu * 1e-6) / 1e12, 2),
+                "frac": round(pf / (pu * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
     else:
         roofline = None
     loss_us = sum(r["us"] for r in table if r["kernel"] == "L1-loss gradient")
