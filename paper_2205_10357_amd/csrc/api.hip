@@ -57,13 +57,13 @@ inline void clear_stale_error() { (void)hipGetLastError(); }
 // backward call used to make some fifteen of them.
 enum Knob {
     K_IGEMM_TILE, K_IGEMM_FAST, K_FAST_TILE, K_FAST_SHORTK, K_FAST_MANY, K_FAST_STAGES, K_WGRAD_SPLITS, K_WGRAD_TARGET,
-    K_SMALLC, K_FILL_UNTOUCHED, K_WGRAD_FAST, K_PACK_FUSED, K_WGRAD_STAGES, K_WGRAD_TICKET, K_PREMASK, K_PANEL, K_PANEL_TILES,
+    K_SMALLC, K_FILL_UNTOUCHED, K_WGRAD_FAST, K_PACK_FUSED, K_WGRAD_STAGES, K_PREMASK, K_PANEL, K_PANEL_TILES,
     K_REDUCE_RIDES, K_COUNT
 };
 const char* const kKnobNames[K_COUNT] = {
     "SOL_IGEMM_TILE", "SOL_IGEMM_FAST", "SOL_FAST_TILE", "SOL_FAST_SHORTK", "SOL_FAST_MANY", "SOL_FAST_STAGES",
     "SOL_WGRAD_SPLITS", "SOL_WGRAD_TARGET", "SOL_SMALLC", "SOL_FILL_UNTOUCHED", "SOL_WGRAD_FAST", "SOL_PACK_FUSED",
-    "SOL_WGRAD_STAGES", "SOL_WGRAD_TICKET", "SOL_PREMASK", "SOL_PANEL", "SOL_PANEL_TILES", "SOL_REDUCE_RIDES"};
+    "SOL_WGRAD_STAGES", "SOL_PREMASK", "SOL_PANEL", "SOL_PANEL_TILES", "SOL_REDUCE_RIDES"};
 constexpr int kKnobUnset = INT32_MIN;
 std::atomic<int> g_knobs[K_COUNT];
 std::atomic<bool> g_knobs_loaded{false};
