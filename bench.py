@@ -132,6 +132,8 @@ def launch_costs(wl, seq, B):
         # a strided 1x1 reads only the sampled pixels
         x_read = x_b if b.k > 1 or b.stride == 1 else n * ho * wo * c_in * 2
         costs[("fwd", b.layer)] = (fl, x_read + w_el * 2 + y_b * (2 if b.res is not None else 1), "x + W + y (+ residual)")
+        if c_in <= 4:        # few-channel layers: a launch that pads the image to 4 channels precedes the GEMM
+            costs[("prepare", b.layer)] = (0, n * h * w * (c_in + 4) * 2, "x + padded x")
         c = calls.get(b.layer)
         if c is None:
             continue
@@ -141,6 +143,11 @@ def launch_costs(wl, seq, B):
         part = max(0, ws - w_el * 2)                       # fp32 partial tiles of the split (the rest: packed weights)
         costs[("wgrad", b.layer)] = (fl, y_b + x_read + part + w_el * 4, "dy + x + partials + packed W written")
         costs[("reduce", b.layer)] = (0, part + w_el * 2 + w_el * 4, "partials + W + dW")
+    for o in wl.ops:
+        if o.op == "maxpool":
+            c, h, w = shp[o.inp]
+            _, ho, wo = shp[o.out]
+            costs[("maxpool", -1)] = (0, n * c * (h * w + ho * wo) * 2, "x + y")
     if wl.train:
         last = wl.conv_blocks()[-1]
         c_out, ho, wo = shp[last.out]
@@ -173,6 +180,10 @@ def per_launch_table(trace, wl, seq, B, steps):
             role = "reduce"
         elif kname == "L1-loss gradient":
             role = "l1"
+        elif kname == "max-pool":
+            role = "maxpool"
+        elif kname == "few-channel prepare":
+            role = "prepare"
         fl, by, what = costs.get((role, tag), (0, 0, ""))
         if kname.endswith("+ split reduction"):        # the launch also carries the reduction of the weight gradient
             by += costs.get(("reduce", tag), (0, 0, ""))[1]

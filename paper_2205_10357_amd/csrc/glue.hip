@@ -192,6 +192,10 @@ hipError_t launch_l1_grad(int dtype, const void* y, const void* t, void* dy, lon
 
 // bf16, channels % 8 == 0: one thread per (output pixel, 8 channels), 16-byte loads and stores.  Comparing the
 // values as floats (bf16 << 16) keeps the result one of the inputs, so no rounding is involved.
+// K > 0: the window edge is k = K, known at compile time: all K * K loads are requested before the first comparison
+// (at coordinates clamped into the image; a tap outside the image then counts as -inf), one memory round trip per
+// thread instead of one per tap.  K == 0: any k, tap by tap.
+template <int K>
 __global__ __launch_bounds__(256) void maxpool_bf16x8_kernel(const bf16_t* x, bf16_t* y, int N, int H, int W, int C, int k,
                                                              int stride, int pad, int Ho, int Wo) {
     const int c8 = C >> 3;
@@ -207,18 +211,37 @@ __global__ __launch_bounds__(256) void maxpool_bf16x8_kernel(const bf16_t* x, bf
     float m[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) m[e] = -INFINITY;
-    for (int kh = 0; kh < k; ++kh) {
-        const int hi = ho * stride - pad + kh;
-        if ((unsigned)hi >= (unsigned)H) continue;
-        for (int kw = 0; kw < k; ++kw) {
-            const int wi = wo * stride - pad + kw;
-            if ((unsigned)wi >= (unsigned)W) continue;
-            const uintx4 v = *reinterpret_cast<const uintx4*>(x + (((long long)n * H + hi) * W + wi) * C + cc * 8);
+    auto take = [&](const uintx4& v, bool inside) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float lo = __uint_as_float(v[e] << 16), hi2 = __uint_as_float(v[e] & 0xffff0000u);
-                m[2 * e] = lo > m[2 * e] ? lo : m[2 * e];
-                m[2 * e + 1] = hi2 > m[2 * e + 1] ? hi2 : m[2 * e + 1];
+        for (int e = 0; e < 4; ++e) {
+            const float lo = inside ? __uint_as_float(v[e] << 16) : -INFINITY;
+            const float hi2 = inside ? __uint_as_float(v[e] & 0xffff0000u) : -INFINITY;
+            m[2 * e] = lo > m[2 * e] ? lo : m[2 * e];
+            m[2 * e + 1] = hi2 > m[2 * e + 1] ? hi2 : m[2 * e + 1];
+        }
+    };
+    if constexpr (K > 0) {
+        uintx4 v[K * K];
+        bool inside[K * K];
+#pragma unroll
+        for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+            for (int kw = 0; kw < K; ++kw) {
+                const int hi = ho * stride - pad + kh, wi = wo * stride - pad + kw;
+                inside[kh * K + kw] = (unsigned)hi < (unsigned)H && (unsigned)wi < (unsigned)W;
+                const int hc = hi < 0 ? 0 : (hi >= H ? H - 1 : hi), wc = wi < 0 ? 0 : (wi >= W ? W - 1 : wi);
+                v[kh * K + kw] = *reinterpret_cast<const uintx4*>(x + (((long long)n * H + hc) * W + wc) * C + cc * 8);
+            }
+#pragma unroll
+        for (int t = 0; t < K * K; ++t) take(v[t], inside[t]);
+    } else {
+        for (int kh = 0; kh < k; ++kh) {
+            const int hi = ho * stride - pad + kh;
+            if ((unsigned)hi >= (unsigned)H) continue;
+            for (int kw = 0; kw < k; ++kw) {
+                const int wi = wo * stride - pad + kw;
+                if ((unsigned)wi >= (unsigned)W) continue;
+                take(*reinterpret_cast<const uintx4*>(x + (((long long)n * H + hi) * W + wi) * C + cc * 8), true);
             }
         }
     }
@@ -233,8 +256,11 @@ hipError_t launch_maxpool(int dtype, const void* x, void* y, int N, int H, int W
     const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
     const long long total = (long long)N * Ho * Wo * C;
     if (total <= 0) return hipSuccess;
-    if (dtype == 1 && (C & 7) == 0)
-        SOL_LAUNCH(maxpool_bf16x8_kernel, dim3(blocks_for(total >> 3)), dim3(256), 0, s, (const bf16_t*)x,
+    if (dtype == 1 && (C & 7) == 0 && k == 3)
+        SOL_LAUNCH(maxpool_bf16x8_kernel<3>, dim3(blocks_for(total >> 3)), dim3(256), 0, s, (const bf16_t*)x,
+                           (bf16_t*)y, N, H, W, C, k, stride, pad, Ho, Wo);
+    else if (dtype == 1 && (C & 7) == 0)
+        SOL_LAUNCH(maxpool_bf16x8_kernel<0>, dim3(blocks_for(total >> 3)), dim3(256), 0, s, (const bf16_t*)x,
                            (bf16_t*)y, N, H, W, C, k, stride, pad, Ho, Wo);
     else if (dtype == 1)
         SOL_LAUNCH(maxpool_kernel<true>, dim3(blocks_for(total)), dim3(256), 0, s, x, y, N, H, W, C, k, stride,

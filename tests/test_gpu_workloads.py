@@ -145,6 +145,30 @@ def test_resnet50_small_elementwise():
     check_chain_elementwise(wl.resnet50_infer_bf16(n=1, hw=64))
 
 
+@pytest.mark.parametrize("geom", [
+    dict(N=2, H=13, W=11, C=16, k=3, stride=2, pad=1),      # the stem's pool: every tap requested at once
+    dict(N=1, H=9, W=10, C=8, k=3, stride=1, pad=1),
+    dict(N=2, H=8, W=12, C=24, k=2, stride=2, pad=0),       # other windows: tap by tap
+    dict(N=1, H=11, W=7, C=8, k=5, stride=2, pad=2),
+    dict(N=1, H=7, W=9, C=12, k=3, stride=2, pad=1),        # channels not a multiple of 8: element by element
+], ids=lambda g: "k{k}s{stride}p{pad}_c{C}".format(**g))
+def test_maxpool_windows_bit_exact(geom):
+    """The max-pool of the glue layer for several windows, strides and channel counts, bf16 and fp32: every output
+    is one of the inputs, so the comparison with the CPU checker is bit for bit."""
+    g = geom
+    r = np.random.default_rng(77)
+    x = wl.snap_to_bf16(r.standard_normal((g["N"], g["C"], g["H"], g["W"])).astype(np.float32))
+    ref = orc.maxpool(x, g["k"], g["stride"], g["pad"])
+    for dt, tdt in ((B.SOL_BF16, torch.bfloat16), (B.SOL_F32, torch.float32)):
+        xd = torch.from_numpy(np.ascontiguousarray(np.transpose(x, (0, 2, 3, 1)))).to("cuda:0").to(tdt)
+        yd = torch.full((g["N"], ref.shape[2], ref.shape[3], g["C"]), 7.0, dtype=tdt, device="cuda:0")
+        B.sol_maxpool_fwd(dt, xd, yd, g["N"], g["H"], g["W"], g["C"], g["k"], g["stride"], g["pad"],
+                          torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        got = np.transpose(yd.float().cpu().numpy().astype(np.float64), (0, 3, 1, 2))
+        assert np.array_equal(got, ref), (geom, dt)
+
+
 # ------------------------------------------------------------------------- full sizes, sampled
 def check_sampled(w, images, n_fwd=400, n_dx=300, dw_layers=(), n_dw=64, n_ch=2, seed=5):
     rng = np.random.default_rng(seed)
