@@ -122,10 +122,6 @@ int pick_igemm_tile(const long long* class_rows, int ncls, int Nc) {
     return order[n - 1];
 }
 
-// Fills tile-dependent fields of the launch (tile counts, class offsets) and launches either the
-// pipelined kernel (source channels % 64 == 0, output channels % 8 == 0, no mask on the gathered
-// operand) or the general one.  SOL_IGEMM_FAST=0 forces the general kernel; SOL_FAST_TILE /
-// SOL_FAST_STAGES override the pipelined kernel's tile and ring depth (tuning experiments).
 // A pipelined or panel launch of `gemm_wgs` workgroups (one per compute unit at a time) can carry the split
 // reduction of the same block's weight gradient along, as workgroups behind its own: as many as its last wave
 // leaves compute units idle, so that the reduction runs beside the tiles instead of after them.  Returns 0 when
@@ -145,6 +141,10 @@ int reduce_rider_blocks(int gemm_wgs, bool small_tile, const ReduceParams* rider
     return idle >= 32 ? idle : 0;
 }
 
+// Fills tile-dependent fields of the launch (tile counts, class offsets) and launches either the
+// pipelined kernel (source channels % 64 == 0, output channels % 8 == 0, no mask on the gathered
+// operand) or the general one.  SOL_IGEMM_FAST=0 forces the general kernel; SOL_FAST_TILE /
+// SOL_FAST_STAGES override the pipelined kernel's tile and ring depth (tuning experiments).
 // `rider`: a split reduction the launch may carry along (see above); *rode tells whether it did.
 int run_igemm(IgemmParams& p, const long long* rows, bool mask, const sol_plan& tuned, hipStream_t stream,
               const ReduceParams* rider = nullptr, bool* rode = nullptr) {
