@@ -139,6 +139,11 @@ def launch_costs(wl, seq, B):
             continue
         dg = y_b + w_el * 2 + x_b + (x_b if c["addend"] is not None else 0) + (x_b if c["dx_mask"] is not None else 0)
         costs[("dgrad", b.layer)] = (fl, dg, "dy + packed W + dx (+ addend) (+ mask)")
+        if b.k < b.stride:   # pixels no tap reaches (1x1 / stride 2: three of four) are written by a launch of their own
+            frac = 1.0 - 1.0 / (b.stride * b.stride)
+            per_pixel = 1 + (c["addend"] is not None) + (c["addend"] is not None and c.get("addend_mask") is not None) + \
+                (c["dx_mask"] is not None)
+            costs[("fill", b.layer)] = (0, int(frac * x_b * per_pixel), "dx (+ addend) (+ masks) on the untouched pixels")
         ws = B.sol_block_workspace_bytes(c["desc"], B.SOL_PASS_BWD)
         part = max(0, ws - w_el * 2)                       # fp32 partial tiles of the split (the rest: packed weights)
         costs[("wgrad", b.layer)] = (fl, y_b + x_read + part + w_el * 4, "dy + x + partials + packed W written")
@@ -184,6 +189,8 @@ def per_launch_table(trace, wl, seq, B, steps):
             role = "maxpool"
         elif kname == "few-channel prepare":
             role = "prepare"
+        elif kname == "tap-less pixel fill":
+            role = "fill"
         fl, by, what = costs.get((role, tag), (0, 0, ""))
         if kname.endswith("+ split reduction"):        # the launch also carries the reduction of the weight gradient
             by += costs.get(("reduce", tag), (0, 0, ""))[1]
