@@ -79,6 +79,14 @@ __device__ __forceinline__ void dma16_buf_to_lds(buffer_rsrc_t rs, unsigned voff
 }
 constexpr unsigned kOutOfRange = 0xffffffffu;    // OR-ed into voff: lane reads zeros
 
+// 16-byte store that writes through the L2 instead of leaving a dirty line there.  A kernel that writes tens of
+// megabytes with plain stores pays for their write-back when it ends (all of its dirty lines at once, after the last
+// workgroup); written through, the same bytes leave while the kernel still computes.  Readers find the data where
+// they found it before (the line stays in L2, clean).
+__device__ __forceinline__ void store16_through(void* dst, uintx4 v) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(dst), "v"(v) : "memory");
+}
+
 // s_waitcnt with vmcnt = N and lgkmcnt = 0 (expcnt untouched): at most N vector-memory
 // operations of this wave still in flight, all of its LDS operations done.
 template <int N>

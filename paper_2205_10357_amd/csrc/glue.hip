@@ -52,7 +52,7 @@ __global__ __launch_bounds__(256) void masked_copy_bf16x8_kernel(const bf16_t* d
     if (i8 >= numel) return;
     if (i8 + 8 <= numel) {
         const uintx4 g = *reinterpret_cast<const uintx4*>(dy + i8);
-        *reinterpret_cast<uintx4*>(dres + i8) = y ? mask_where_positive(g, *reinterpret_cast<const uintx4*>(y + i8)) : g;
+        store16_through(dres + i8, y ? mask_where_positive(g, *reinterpret_cast<const uintx4*>(y + i8)) : g);
     } else {
         for (long long i = i8; i < numel; ++i) dres[i] = (!y || (short)y[i] > 0) ? dy[i] : (bf16_t)0;
     }
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(256) void l1_grad_kernel(const void* yv, const void
                 const float hi = grad(__uint_as_float(y4[e] & 0xffff0000u), __uint_as_float(t4[e] & 0xffff0000u));
                 o[e] = pack_bf16x2(lo, hi);
             }
-            *reinterpret_cast<uintx4*>(db + i8) = o;
+            store16_through(db + i8, o);
         } else {
             for (long long i = i8; i < numel; ++i) db[i] = f32_to_bf16(grad(bf16_to_f32(yb[i]), bf16_to_f32(tb[i])));
         }
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(256) void untouched_pixels_kernel(bf16_t* dx, const
         if (addend_mask) v = mask_where_positive(v, *reinterpret_cast<const uintx4*>(addend_mask + idx * 8));
     }
     if (out_mask) v = mask_where_positive(v, *reinterpret_cast<const uintx4*>(out_mask + idx * 8));
-    *reinterpret_cast<uintx4*>(dx + idx * 8) = v;
+    store16_through(dx + idx * 8, v);
 }
 
 static inline unsigned blocks_for(long long total) { return (unsigned)((total + 255) / 256); }
@@ -248,7 +248,7 @@ __global__ __launch_bounds__(256) void maxpool_bf16x8_kernel(const bf16_t* x, bf
     uintx4 o;
 #pragma unroll
     for (int e = 0; e < 4; ++e) o[e] = (__float_as_uint(m[2 * e]) >> 16) | (__float_as_uint(m[2 * e + 1]) & 0xffff0000u);
-    *reinterpret_cast<uintx4*>(y + idx * 8) = o;
+    store16_through(y + idx * 8, o);
 }
 
 hipError_t launch_maxpool(int dtype, const void* x, void* y, int N, int H, int W, int C, int k, int stride, int pad,

@@ -512,7 +512,7 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p) {
         uintx4 out = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
                       pack_bf16x2(v[6], v[7])};
         if (has_outmask) out = mask_where_positive(out, outm[ps]);
-        if (ovalid[ps]) *reinterpret_cast<uintx4*>(p.out + oofs[ps]) = out;
+        if (ovalid[ps]) store16_through(p.out + oofs[ps], out);
     }
 }
 

@@ -90,7 +90,7 @@ __device__ __forceinline__ void reduce_rows_vec(const ReduceParams& p, int block
                     for (int e = 0; e < 4; ++e) dot = fmaf(w[c][e], g[c][e], dot);
                     floatx4 d = {sc * g[c][0], sc * g[c][1], sc * g[c][2], sc * g[c][3]};
                     if (p.accumulate) d += *reinterpret_cast<const floatx4*>(p.dW + row + kc);
-                    *reinterpret_cast<floatx4*>(p.dW + row + kc) = d;
+                    store16_through(p.dW + row + kc, __builtin_bit_cast(uintx4, d));
                 }
             }
         }

@@ -179,7 +179,7 @@ __global__ __launch_bounds__(256, 2) void smallc_fwd_kernel(const SmallCParams p
                 const int px = e >> 3, c = e & 7;
                 if (px < valid) {
                     const uintx2 a = outs[px * OP + 2 * c], b = outs[px * OP + 2 * c + 1];
-                    *reinterpret_cast<uintx4*>(dst + px * SC_CO + c * 8) = uintx4{a[0], a[1], b[0], b[1]};
+                    store16_through(dst + px * SC_CO + c * 8, uintx4{a[0], a[1], b[0], b[1]});
                 }
             }
         }

@@ -254,8 +254,8 @@ __global__ __launch_bounds__(256) void wgrad_fast_kernel(const WgradParams p) {
         const int row = r0 + 8 * ps;
         const int co = co0 + row, k = k0 + kq;
         if (co < p.C_out && k < p.K)
-            *reinterpret_cast<floatx4*>(part + (long long)co * p.K + k) =
-                *reinterpret_cast<const floatx4*>(stg + row * WGF_LDW + kq);
+            store16_through(part + (long long)co * p.K + k,
+                            __builtin_bit_cast(uintx4, *reinterpret_cast<const floatx4*>(stg + row * WGF_LDW + kq)));
     }
 }
 
