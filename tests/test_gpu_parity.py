@@ -241,6 +241,27 @@ def test_random_layer_shapes_on_the_pipelined_kernels(idx):
     show(f"random shape {idx}", errs)
 
 
+@pytest.mark.parametrize("idx", range(len(RANDOM_SHAPES)), ids=lambda i: "k{K}s{stride}p{pad}_{C_in}to{C_out}_{N}x{H}x{W}".format(**RANDOM_SHAPES[i]))
+def test_random_layer_shapes_riding_reduction_changes_no_bit(idx, sol_env):
+    """The same shapes with the split reduction as the library places it (riding with the data-gradient launch where
+    the launch can carry it), with a forced odd number of riding workgroups, and as a launch of its own: dx, dW,
+    dscale and dshift are the same bits in all three."""
+    shape = RANDOM_SHAPES[idx]
+    case = pu.make_case(300 + idx, **shape)
+    r = np.random.default_rng(400 + idx)
+    dxm = wl.snap_to_bf16(np.maximum(r.standard_normal(case["x"].shape), 0).astype(np.float32))
+    ad = wl.snap_to_bf16(r.standard_normal(case["x"].shape).astype(np.float32))
+    out = {}
+    for mode in (1, 7, 0):
+        sol_env("SOL_REDUCE_RIDES", mode)
+        print(f"[random shape {idx}] {shape} SOL_REDUCE_RIDES={mode}", flush=True)
+        out[mode] = pu.gpu_block(case, addend=ad, dx_mask=dxm, premasked=True)
+    for mode in (1, 7):
+        for key in ("dx", "dW", "dscale", "dshift"):
+            a, b = out[mode][key], out[0][key]
+            assert np.array_equal(a, b), f"SOL_REDUCE_RIDES={mode}, {key}: {int((a != b).sum())} elements differ"
+
+
 @pytest.mark.parametrize("tile", [0, 1, 2, 3])
 def test_bf16_every_tile_shape(tile, sol_env):
     sol_env("SOL_IGEMM_TILE", tile)
