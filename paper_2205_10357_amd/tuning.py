@@ -96,17 +96,17 @@ def tune(seq: Sequencer, iters: int = 20, margin: float = 0.03) -> Dict[str, Dic
         c = bwd_calls.get(o.layer)
         if c is not None:
             g = seq.grads[o.layer]
+            # Both gradients are timed in the call the sequencer issues: one backward call for dx and dW together.  Its
+            # launches share work (the weight re-pack rides with the weight gradient, the split reduction with the data
+            # gradient), so a plan that wins for one branch alone can lose in the call.
+            def backward():
+                B.sol_block_bwd(c["desc"], c["dy"], seq.act[o.inp], p["W"], None, c["dx"], g["dW"], g["dscale"],
+                                g["dshift"], p["scale"], None, c["addend"], None, c["dx_mask"], seq.ws, None)
             if c["dx"] is not None and d.stride * d.stride <= 4:
-                def dgrad():
-                    B.sol_block_bwd(c["desc"], c["dy"], seq.act[o.inp], p["W"], None, c["dx"], None, None, None,
-                                    p["scale"], None, c["addend"], None, c["dx_mask"], seq.ws, None)
                 in_rows = d.N * d.H * d.W
                 cand = GEMM_CANDIDATES + (LARGE_TILE_CANDIDATES if in_rows >= 256 * 256 else [])
-                entry["dgrad"] = _best(c["desc"], B.SOL_PLAN_DGRAD, [(t, s, 0) for t, s in cand], dgrad, iters, margin)
-
-            def wgrad():
-                B.sol_block_bwd(c["desc"], c["dy"], seq.act[o.inp], p["W"], None, None, g["dW"], g["dscale"],
-                                g["dshift"], p["scale"], None, None, None, None, seq.ws, None)
+                entry["dgrad"] = _best(c["desc"], B.SOL_PLAN_DGRAD, [(t, s, 0) for t, s in cand], backward, iters, margin)
+            wgrad = backward
 
             def grow_workspace():               # more splits need more room for the fp32 partial tiles
                 need = B.sol_block_workspace_bytes(c["desc"], B.SOL_PASS_BWD)
